@@ -1,0 +1,254 @@
+/*
+ * CPU oracle for relay-buffer-free MoE dispatch and combine.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, single-threaded
+ * definition that the HIP library is checked against.  It shares no code with
+ * the HIP path, is never linked into or called from the product library, and
+ * may only be used by the tests, the smoke check and the benchmark's
+ * cpu_baseline leg.
+ *
+ * Every function follows the paper's own order and notation (Section 5.1 for
+ * the symbols; Algorithm 1 / Section 5.2 for the prefill chain; Algorithm 2 /
+ * Section 5.3 for decode, which computes the same values in one procedure).
+ * No blocking, fusion or reordering beyond those definitions.
+ *
+ * Readings taken where the paper is silent (all listed in the design notes):
+ *   - "before" in the definition of s means smaller flat index i = t*k + j;
+ *   - one source rank, so the large offset o_{e,r} has a single column and is
+ *     an exclusive prefix sum of the expert counts inside each rank region;
+ *   - combine reads the same row that dispatch wrote (q = p);
+ *   - id -1 marks an unused slot (skipped, not counted); any other id outside
+ *     [0,E) is skipped and counted in status[0];
+ *   - windows are tight (region r holds exactly c_rank[r] rows) unless a fixed
+ *     region stride is given, in which case region r starts at r*stride and
+ *     branches that do not fit are dropped and counted in status[1];
+ *   - combine accumulates in fp32 starting from +0, ascending j, one fused
+ *     multiply-add per branch, then rounds once (nearest-even) to the storage
+ *     type.  An fp64 variant is provided as an independent check.
+ *
+ * Parity pins: counts/offsets/s/row_map/dispatch are pinned by brute force,
+ * numpy bincount/cumsum/stable-argsort and hand-worked fixtures; combine by
+ * identity-expert closed forms, an fp64 numpy reference and torch's bf16
+ * rounding.  Absolute values against the authors' Ascend implementation:
+ * parity unpinned (the paper prints no tensors).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+enum { MOE_REF_BF16 = 0, MOE_REF_F32 = 1 };
+
+/* ---- storage conversions -------------------------------------------------- */
+
+static float bf16_to_f32(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+/* fp32 -> bf16, round to nearest, ties to even; NaN stays a quiet NaN. */
+static uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  uint32_t lsb = (u >> 16) & 1u;
+  u += 0x7FFFu + lsb;
+  return (uint16_t)(u >> 16);
+}
+
+/* fp64 -> bf16 with a single nearest-even rounding, done on the double itself:
+ * normal range: keep 7 explicit mantissa bits of the double; below 2^-126 the bf16
+ * grid is the fixed subnormal spacing 2^-133. */
+static uint16_t f64_to_bf16_rne(double d) {
+  if (d != d) return 0x7FC0u;
+  const double a = fabs(d);
+  double r;
+  if (a < 0x1p-126) {
+    r = nearbyint(a * 0x1p133) * 0x1p-133;
+  } else if (isinf(a)) {
+    r = a;
+  } else {
+    uint64_t u;
+    memcpy(&u, &a, 8);
+    const uint64_t lsb = (u >> 45) & 1ull;
+    u += ((1ull << 44) - 1ull) + lsb;
+    u &= ~((1ull << 45) - 1ull);
+    memcpy(&r, &u, 8);
+  }
+  const float f = (float)r; /* exact, or +inf when r reached 2^128 */
+  uint32_t v;
+  memcpy(&v, &f, 4);
+  uint16_t h = (uint16_t)(v >> 16);
+  if (signbit(d)) h |= 0x8000u;
+  return h;
+}
+
+/* ---- Layout + Notify (Section 5.2; eq. for c^rank, c^exp, s; Section 5.1 rule row = o + s) */
+
+int moe_ref_plan(int32_t T, int32_t k, int32_t E, int32_t R, int64_t region_stride_rows,
+                 const int32_t *K,          /* [T*k]  routing ids */
+                 int32_t *c_exp,            /* [E]    out */
+                 int32_t *c_rank,           /* [R]    out */
+                 int32_t *expert_offset,    /* [E+1]  out: o */
+                 int32_t *region_base,      /* [R+1]  out */
+                 int32_t *s,                /* [T*k]  out: small offset, -1 if skipped */
+                 int32_t *row_map,          /* [T*k]  out: o[K] + s, -1 if skipped/dropped */
+                 int32_t *status)           /* [2]    out: {#invalid ids, #dropped for capacity} */
+{
+  if (T < 0 || k < 1 || E < 1 || R < 1 || E % R != 0) return -2;
+  const int32_t Er = E / R;
+  status[0] = 0;
+  status[1] = 0;
+  for (int32_t e = 0; e < E; ++e) c_exp[e] = 0;
+
+  /* Layout: running per-expert counter == number of earlier branches with the same expert */
+  for (int32_t t = 0; t < T; ++t) {
+    for (int32_t j = 0; j < k; ++j) {
+      const int64_t i = (int64_t)t * k + j;
+      const int32_t e = K[i];
+      if (e == -1) { s[i] = -1; continue; }
+      if (e < 0 || e >= E) { status[0] += 1; s[i] = -1; continue; }
+      s[i] = c_exp[e];
+      c_exp[e] += 1;
+    }
+  }
+  /* destination rank of expert e is floor(e / E_r) */
+  for (int32_t r = 0; r < R; ++r) {
+    int32_t acc = 0;
+    for (int32_t e = r * Er; e < (r + 1) * Er; ++e) acc += c_exp[e];
+    c_rank[r] = acc;
+  }
+  /* Notify, single source rank: region bases, then expert blocks inside each region */
+  region_base[0] = 0;
+  for (int32_t r = 0; r < R; ++r) {
+    if (region_stride_rows > 0) region_base[r + 1] = (int32_t)((int64_t)(r + 1) * region_stride_rows);
+    else region_base[r + 1] = region_base[r] + c_rank[r];
+  }
+  for (int32_t r = 0; r < R; ++r) {
+    int32_t run = region_base[r];
+    for (int32_t e = r * Er; e < (r + 1) * Er; ++e) {
+      expert_offset[e] = run;
+      run += c_exp[e];
+    }
+  }
+  expert_offset[E] = expert_offset[E - 1] + c_exp[E - 1];
+  /* two-level rule */
+  for (int64_t i = 0; i < (int64_t)T * k; ++i) {
+    if (s[i] < 0) { row_map[i] = -1; continue; }
+    const int32_t e = K[i];
+    const int32_t row = expert_offset[e] + s[i];
+    if (region_stride_rows > 0 && row >= region_base[e / Er + 1]) {
+      status[1] += 1;
+      row_map[i] = -1;
+    } else {
+      row_map[i] = row;
+    }
+  }
+  return 0;
+}
+
+/* ---- Dispatch (Algorithm 1, first loop; Section 5.2 "Prefill Dispatch") ---- */
+
+int moe_ref_dispatch(int32_t T, int32_t H, int32_t k, int32_t elem_bytes,
+                     const void *X,             /* [T, H] */
+                     const int32_t *row_map,    /* [T*k]  */
+                     void *window)              /* [rows, H]; only mapped rows are written */
+{
+  const size_t row_bytes = (size_t)H * (size_t)elem_bytes;
+  for (int32_t t = 0; t < T; ++t) {
+    for (int32_t j = 0; j < k; ++j) {
+      const int32_t p = row_map[(int64_t)t * k + j];
+      if (p < 0) continue;
+      memcpy((char *)window + (size_t)p * row_bytes, (const char *)X + (size_t)t * row_bytes, row_bytes);
+    }
+  }
+  return 0;
+}
+
+/* ---- Combine (Algorithm 1, second loop; Section 5.2 "Prefill Combine") ----- */
+
+int moe_ref_combine(int32_t T, int32_t H, int32_t k, int32_t dtype,
+                    const void *Yexp,          /* [rows, H] expert outputs, window layout */
+                    const float *W,            /* [T*k] gate weights */
+                    const int32_t *row_map,    /* [T*k] */
+                    void *Y)                   /* [T, H] out */
+{
+  if (dtype != MOE_REF_BF16 && dtype != MOE_REF_F32) return -2;
+  for (int32_t t = 0; t < T; ++t) {
+    for (int32_t h = 0; h < H; ++h) {
+      float acc = 0.0f;
+      for (int32_t j = 0; j < k; ++j) {
+        const int32_t q = row_map[(int64_t)t * k + j];
+        if (q < 0) continue;
+        const size_t idx = (size_t)q * (size_t)H + (size_t)h;
+        const float y = dtype == MOE_REF_BF16 ? bf16_to_f32(((const uint16_t *)Yexp)[idx])
+                                              : ((const float *)Yexp)[idx];
+        acc = fmaf(W[(int64_t)t * k + j], y, acc);
+      }
+      const size_t o = (size_t)t * (size_t)H + (size_t)h;
+      if (dtype == MOE_REF_BF16) ((uint16_t *)Y)[o] = f32_to_bf16_rne(acc);
+      else ((float *)Y)[o] = acc;
+    }
+  }
+  return 0;
+}
+
+/* Same sum carried in fp64 (each product of an fp32 weight and a bf16/fp32 value is
+ * exact in fp64), rounded once to the storage type: the mathematical value of the
+ * combine equation, used to bound the fp32 path. */
+int moe_ref_combine_f64(int32_t T, int32_t H, int32_t k, int32_t dtype, const void *Yexp,
+                        const float *W, const int32_t *row_map, void *Y)
+{
+  if (dtype != MOE_REF_BF16 && dtype != MOE_REF_F32) return -2;
+  for (int32_t t = 0; t < T; ++t) {
+    for (int32_t h = 0; h < H; ++h) {
+      double acc = 0.0;
+      for (int32_t j = 0; j < k; ++j) {
+        const int32_t q = row_map[(int64_t)t * k + j];
+        if (q < 0) continue;
+        const size_t idx = (size_t)q * (size_t)H + (size_t)h;
+        const double y = dtype == MOE_REF_BF16 ? (double)bf16_to_f32(((const uint16_t *)Yexp)[idx])
+                                               : (double)((const float *)Yexp)[idx];
+        acc += (double)W[(int64_t)t * k + j] * y;
+      }
+      const size_t o = (size_t)t * (size_t)H + (size_t)h;
+      if (dtype == MOE_REF_BF16) ((uint16_t *)Y)[o] = f64_to_bf16_rne(acc);
+      else ((float *)Y)[o] = (float)acc;
+    }
+  }
+  return 0;
+}
+
+/* ---- Stand-in for the expert FFNs (not part of the method) -----------------
+ * Yexp[row] = round(f32(window[row]) * scale[e]) for the row of every placed branch
+ * routed to expert e.  The real FFNs need trained weights; a per-expert scalar keeps
+ * rows attributable to their expert. */
+int moe_ref_expert_standin(int32_t T, int32_t H, int32_t k, int32_t dtype, const int32_t *K,
+                           const int32_t *row_map, const float *scale, const void *window, void *Yexp)
+{
+  if (dtype != MOE_REF_BF16 && dtype != MOE_REF_F32) return -2;
+  for (int64_t i = 0; i < (int64_t)T * k; ++i) {
+    const int32_t row = row_map[i];
+    if (row < 0) continue;
+    const float sc = scale[K[i]];
+    for (int32_t h = 0; h < H; ++h) {
+      const size_t idx = (size_t)row * (size_t)H + (size_t)h;
+      if (dtype == MOE_REF_BF16) {
+        const float v = bf16_to_f32(((const uint16_t *)window)[idx]) * sc;
+        ((uint16_t *)Yexp)[idx] = f32_to_bf16_rne(v);
+      } else {
+        ((float *)Yexp)[idx] = ((const float *)window)[idx] * sc;
+      }
+    }
+  }
+  return 0;
+}
+
+/* storage conversions, exported so tests can pin them against an independent library */
+void moe_ref_f32_to_bf16(const float *in, uint16_t *out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = f32_to_bf16_rne(in[i]);
+}
+void moe_ref_f64_to_bf16(const double *in, uint16_t *out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = f64_to_bf16_rne(in[i]);
+}
