@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the relay-buffer-free MoE dispatch + combine path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch:
+    prefill schedule : moe_plan -> moe_dispatch -> moe_combine   (3 calls, 4 kernels)
+    decode schedule  : moe_dispatch (plan fused) -> moe_combine  (2 calls, 2 kernels)
+with all inputs resident in HBM.  The stand-in expert that fills expert_out runs once, untimed.
+`value` = algorithmic payload bytes of one step, 2*T*H*b*(1+k), divided by the step time.
+
+Prints ONE JSON line on stdout (headline workload); details go to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E published peak
+DESCR = {
+    "prefill": "prefill balanced: T=4096 H=7168 bf16, E=256 in R=32 regions, top-8 uniform",
+    "decode": "decode: T=128 H=7168 bf16, E=256 in R=32 regions, top-8 uniform",
+    "skewed": "prefill skewed: T=16384 H=7168 bf16, E=256 in R=32 regions, top-8 Zipf(1.2)",
+    "wide": "prefill wide: T=32768 H=4096 bf16, E=128 in R=16 regions, group-limited top-8",
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def event_time_ms(fn, iters):
+    """Average duration of fn() over `iters` back-to-back calls, HIP events on the launch stream."""
+    import torch
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(iters):
+        fn(i)
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+class Sets:
+    """`n` disjoint buffer sets of one workload (rotating through them keeps small working sets
+    out of the 256 MB Infinity Cache between steps)."""
+
+    def __init__(self, cfg, n):
+        import torch
+        import workloads as wl
+        import paper_2605_06055_amd as moe
+        from paper_2605_06055_amd.layer import MoeLayer, to_device
+        self.cfg, self.n, self.moe = cfg, n, moe
+        self.layers, self.x, self.k, self.w = [], [], [], []
+        for i in range(n):
+            w = wl.make(cfg, seed=cfg.seed + i)
+            layer = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, dtype=cfg.dtype)
+            xd, kd, wd = to_device(w.X), to_device(w.K), to_device(w.W)
+            layer.dispatch(xd, kd)
+            layer.standin_expert(kd, to_device(w.scale))
+            self.layers.append(layer), self.x.append(xd), self.k.append(kd), self.w.append(wd)
+        torch.cuda.synchronize()
+        self.schedule = self.layers[0].schedule
+
+    def step(self, i):
+        j = i % self.n
+        L = self.layers[j]
+        L.dispatch(self.x[j], self.k[j])
+        L.combine(self.w[j])
+
+    def plan_only(self, i):
+        j = i % self.n
+        L = self.layers[j]
+        self.moe.moe_plan(L.shape, self.k[j], L._plan_struct)
+
+    def dispatch_only(self, i):
+        j = i % self.n
+        L = self.layers[j]
+        self.moe.moe_dispatch(L.shape, self.x[j], self.k[j], L._plan_struct, L.window)
+
+    def combine_only(self, i):
+        j = i % self.n
+        self.layers[j].combine(self.w[j])
+
+
+def measure(cfg, steps, warmup, n_sets):
+    import paper_2605_06055_amd as moe
+    s = Sets(cfg, n_sets)
+    for i in range(warmup):
+        s.step(i)
+    ms = event_time_ms(s.step, steps)
+    res = {"ms_per_step": ms, "us_per_layer": ms * 1e3, "gbs": cfg.payload_bytes / (ms * 1e-3) / 1e9,
+           "schedule": "decode" if s.schedule == moe.MOE_SCHEDULE_DECODE else "prefill", "buffer_sets": n_sets}
+    half = cfg.T * cfg.H * cfg.elem_bytes * (1 + cfg.k)           # bytes of dispatch alone == combine alone
+    kern = {}
+    if s.schedule == moe.MOE_SCHEDULE_PREFILL:
+        kern["plan_us"] = event_time_ms(s.plan_only, steps) * 1e3
+    kern["dispatch_us"] = event_time_ms(s.dispatch_only, steps) * 1e3
+    kern["combine_us"] = event_time_ms(s.combine_only, steps) * 1e3
+    kern["dispatch_gbs"] = half / kern["dispatch_us"] / 1e3
+    kern["combine_gbs"] = half / kern["combine_us"] / 1e3
+    res["kernels"] = kern
+    res["half_bytes"] = half
+    return res
+
+
+def cpu_baseline(cfg, budget_s=12.0):
+    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+    import oracle
+    import workloads as wl
+    T = min(cfg.T, 2048)                           # a slice of the batch keeps the leg to seconds
+    sub = cfg.with_(T=T)
+    w = wl.make(sub)
+    reps, spent = 0, 0.0
+    while reps < 1 or (spent < budget_s and reps < 50):
+        t0 = time.perf_counter()
+        pl = oracle.plan(w.K, sub.E, sub.R)
+        window = oracle.dispatch(w.X, pl.row_map, pl.window_rows)
+        oracle.combine(window, w.W, pl.row_map)
+        spent += time.perf_counter() - t0
+        reps += 1
+    per = spent / reps
+    return {"value": sub.payload_bytes / per / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {T} tokens of the workload (plan+dispatch+combine, identity expert), "
+                      f"{reps} repetitions, {per * 1e3:.1f} ms each", "host_cpus": os.cpu_count()}
+
+
+def traffic_for(kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc (committed summary), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        return json.load(open(path)).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="prefill", choices=sorted(DESCR))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode T=128 leg of the headline run")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the dispatch/combine path; this build has no multi-GPU "
+              "path (no collectives are part of it). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    import paper_2605_06055_amd as moe
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    moe.load_library()
+    torch.cuda.set_device(0)
+
+    cfg = wl.CONFIGS[args.workload]
+    n_sets = 20 if cfg.payload_bytes < 512e6 else 1
+    main_res = measure(cfg, args.steps, args.warmup, n_sets)
+    log(f"[{args.workload}] {json.dumps(main_res)}")
+
+    kern = main_res["kernels"]
+    dom = "moe_combine" if kern["combine_us"] >= kern["dispatch_us"] else "moe_dispatch"
+    dom_us = max(kern["combine_us"], kern["dispatch_us"])
+    achieved = main_res["half_bytes"] / dom_us / 1e3
+    out = {
+        "metric": "dispatch+combine effective HBM GB/s", "value": round(main_res["gbs"], 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(main_res["ms_per_step"], 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": DESCR[args.workload], "schedule": main_res["schedule"],
+                   "payload_bytes_per_step": cfg.payload_bytes, "accumulate": "fp32", "buffer_sets": n_sets},
+        "us_per_layer": round(main_res["us_per_layer"], 2),
+        "frac_of_hbm_peak": round(main_res["gbs"] / HBM_PEAK_GBS, 4),
+        "kernels": {k: round(v, 2) for k, v in kern.items()},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": traffic_for(f"{dom}:{args.workload}")},
+    }
+    if args.workload == "prefill" and not args.no_decode:
+        dcfg = wl.CONFIGS["decode"]
+        d = measure(dcfg, max(args.steps, 200), args.warmup, 20)
+        log(f"[decode] {json.dumps(d)}")
+        out["decode"] = {"workload": DESCR["decode"], "us_per_layer": round(d["us_per_layer"], 2),
+                         "value": round(d["gbs"], 1), "unit": "GB/s",
+                         "frac_of_hbm_peak": round(d["gbs"] / HBM_PEAK_GBS, 4), "buffer_sets": d["buffer_sets"],
+                         "cache": "cold: 20 disjoint buffer sets (660 MB) rotated so no step finds its lines in "
+                                  "the 256 MB Infinity Cache",
+                         "kernels": {k: round(v, 2) for k, v in d["kernels"].items()}}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+        out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

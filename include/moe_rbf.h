@@ -1,0 +1,140 @@
+/*
+ * moe_rbf -- relay-buffer-free MoE dispatch and combine for AMD MI355X (gfx950).
+ *
+ * One device's share of the paper's communication path: routing ids are turned
+ * into counts, offsets and a stable row map; dispatch copies every token row
+ * straight into its destination expert window; combine reads the k expert-output
+ * rows of a token back out of the windows and reduces them with the gate weights,
+ * writing in token order.  There is no staging, relay or un-permute buffer.
+ *
+ * Notation (paper, Section 5.1 and Table 1): T tokens, hidden size H, routing
+ * degree k, E experts on R ranks, E_r = E/R experts per rank; X[T,H] hidden
+ * states, K[T,k] routing ids, W[T,k] gate weights; c^exp, c^rank branch counts;
+ * s small offset; o large offset; expert-window row = o + s.
+ * The R rank windows are R contiguous row regions of ONE device buffer that
+ * stands in for the remote windows of a pooled-HBM system.
+ *
+ * General conventions
+ *   - Every pointer named "device" must be device memory of the current HIP
+ *     device, owned by the caller, 16-byte aligned.  The library allocates and
+ *     frees nothing, copies nothing between host and device and never
+ *     synchronises: all work is enqueued on the caller's stream and results are
+ *     valid once that stream reaches the end of the call's work.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - moe_shape and moe_plan_t are read on the host during the call only.
+ *   - All tensors are row-major and dense.  X, window, expert_out and Y share
+ *     `dtype`; K is int32; W is float32; all counts and offsets are int32.
+ *   - Return value: MOE_OK or a negative moe_status.  All error returns are
+ *     decided on the host BEFORE anything is enqueued (so a failed call has no
+ *     effect), except MOE_ERR_LAUNCH which reports that the HIP runtime refused a kernel launch.
+ *   - Data-dependent problems cannot be returned without a synchronisation; they
+ *     are recorded in the device words plan->status[0..1] (see moe_plan).
+ */
+#ifndef MOE_RBF_H
+#define MOE_RBF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum moe_dtype { MOE_DTYPE_BF16 = 0, MOE_DTYPE_F32 = 1 };
+
+/* Two schedules compute the same values (paper, Section 4):
+ *   PREFILL: explicit Layout -> Notify -> Dispatch -> Combine; moe_plan must run before moe_dispatch.
+ *   DECODE : counts, offsets and row map are produced inside the dispatch kernel.
+ *   AUTO   : DECODE iff T*k <= MOE_AUTO_DECODE_MAX_BRANCHES. */
+enum moe_schedule { MOE_SCHEDULE_AUTO = 0, MOE_SCHEDULE_PREFILL = 1, MOE_SCHEDULE_DECODE = 2 };
+
+enum moe_status {
+  MOE_OK = 0,
+  MOE_ERR_NULL = -1,       /* a required pointer is NULL */
+  MOE_ERR_SHAPE = -2,      /* T<0, H<1, k<1, E<1, R<1, E%R!=0, E>MOE_MAX_EXPERTS, negative stride, unknown
+                              dtype/schedule, or DECODE forced with T*k > MOE_DECODE_MAX_BRANCHES */
+  MOE_ERR_ALIGN = -3,      /* H*elem_bytes not a multiple of 16, or a device pointer not 16-byte aligned */
+  MOE_ERR_OVERFLOW = -4,   /* T*k or the window row count does not fit in int32 */
+  MOE_ERR_WORKSPACE = -5,  /* plan->workspace missing or smaller than moe_workspace_bytes */
+  MOE_ERR_LAUNCH = -6      /* the HIP runtime refused a kernel launch */
+};
+
+#define MOE_MAX_EXPERTS 1024
+#define MOE_AUTO_DECODE_MAX_BRANCHES 2048
+#define MOE_DECODE_MAX_BRANCHES 8192
+
+typedef struct moe_shape {
+  int32_t T;                  /* tokens (0 is legal: counts are zeroed, nothing else happens) */
+  int32_t H;                  /* hidden size, elements */
+  int32_t k;                  /* routing degree; ids may repeat inside a token, so k > E is legal */
+  int32_t E;                  /* experts, 1..MOE_MAX_EXPERTS */
+  int32_t R;                  /* rank regions; E % R == 0 */
+  int32_t dtype;              /* moe_dtype of X / window / expert_out / Y */
+  int32_t schedule;           /* moe_schedule */
+  int32_t reserved;           /* must be 0 */
+  int64_t region_stride_rows; /* 0: tight windows, region r holds exactly c^rank[r] rows and the window has T*k rows.
+                                 >0: symmetric windows, region r starts at row r*stride; branches that do not fit
+                                 in their region are not placed (row_map = -1) and are counted in status[1]. */
+} moe_shape;
+
+/* Plan state (paper, Table 1).  All pointers are DEVICE pointers owned by the caller.
+ * Written by moe_plan (PREFILL) or by moe_dispatch (DECODE); read by moe_dispatch (PREFILL) and moe_combine. */
+typedef struct moe_plan_t {
+  int32_t *expert_count;  /* [E]    c^exp: routed branches per expert (perExpertTokenNum; also the per-expert
+                                    receive counts n^exp for the single source rank) */
+  int32_t *rank_count;    /* [R]    c^rank: routed branches per destination rank (perRankTokenNum; n^recv of region r) */
+  int32_t *expert_offset; /* [E+1]  o: first window row of expert e's block (putOffset / ep_recv_count);
+                                    [E] = one past the last expert's block */
+  int32_t *region_base;   /* [R+1]  first window row of rank region r; [R] = window row count */
+  int32_t *send_idx;      /* [T*k]  s / delta: position of the branch inside its expert's stream, counting branches
+                                    with smaller flat index t*k+j and the same expert (sendTokenIdx / expandIdx);
+                                    -1 for skipped ids.  May be NULL: then it is not written. */
+  int32_t *row_map;       /* [T*k]  window row of the branch = expert_offset[K] + send_idx; -1 = not placed */
+  int32_t *status;        /* [2]    {number of ids outside [0,E) other than -1, number of branches dropped for
+                                    region capacity}.  Id -1 marks an unused slot and is not an error. */
+  void *workspace;        /* device scratch for moe_plan, >= moe_workspace_bytes(shape); unused by DECODE dispatch */
+  size_t workspace_bytes;
+} moe_plan_t;
+
+/* Bytes of plan->workspace that moe_plan needs for this shape (multiple of 256, never 0). */
+int moe_workspace_bytes(const moe_shape *shape, size_t *out_bytes);
+
+/* Rows the window / expert_out buffers must hold: T*k (tight) or R*region_stride_rows. */
+int moe_window_rows(const moe_shape *shape, int64_t *out_rows);
+
+/* Which schedule moe_dispatch will use for this shape (resolves AUTO). */
+int moe_resolve_schedule(const moe_shape *shape, int32_t *out_schedule);
+
+/* Prefill Layout + Notify (paper, Section 5.2; Algorithm 1 steps "Layout" and "Notify", single source rank).
+ *   topk_idx : device, int32 [T*k], read only.
+ *   Writes every array of `plan` (send_idx only if non-NULL) and zero-initialises status itself.
+ *   Moves no payload.  Results do not depend on the launch configuration. */
+int moe_plan(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream);
+
+/* Dispatch (paper, Section 5.2 "Prefill Dispatch" / Section 5.3 "Decode Dispatch"; first loop of
+ * Algorithms 1 and 2): window[row_map[t,j], :] = X[t, :] for every placed branch.
+ *   x        : device, [T,H] of shape->dtype, read only.
+ *   topk_idx : device, int32 [T*k]; read by the DECODE schedule only (may be NULL for PREFILL).
+ *   plan     : PREFILL reads row_map; DECODE writes all of the plan exactly as moe_plan would.
+ *   window   : device, [moe_window_rows, H]; only rows some branch maps to are written.
+ *   x and window must not overlap. */
+int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx, moe_plan_t *plan,
+                 void *window, void *stream);
+
+/* Combine (paper, Section 5.2 "Prefill Combine" / Section 5.3 "Decode Combine"; second loop of
+ * Algorithms 1 and 2): Y[t,:] = sum_j W[t,j] * expert_out[row_map[t,j], :].
+ *   Accumulation is fp32 from +0 in ascending j with one fused multiply-add per placed branch and a single
+ *   round-to-nearest-even to shape->dtype; unplaced branches (row_map = -1) are skipped.
+ *   expert_out : device, window layout, read only (may be the window buffer itself).
+ *   topk_w     : device, float32 [T*k].
+ *   y          : device, [T,H], every row written; must not overlap expert_out. */
+int moe_combine(const moe_shape *shape, const void *expert_out, const float *topk_w, const moe_plan_t *plan,
+                void *y, void *stream);
+
+/* Static string for a moe_status value. */
+const char *moe_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_RBF_H */

@@ -1,0 +1,180 @@
+// C-ABI boundary of the library: argument validation on the host, then kernel launches on the
+// caller's stream.  Nothing here allocates, copies between host and device, or synchronises.
+#include <hip/hip_runtime.h>
+
+#include "launch.h"
+#include "moe_rbf.h"
+
+using namespace moe_rbf;
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int elem_bytes(int dtype) { return dtype == MOE_DTYPE_BF16 ? 2 : 4; }
+
+// Shape checks shared by every entry point.  Fills `d` on success.
+int check_shape(const moe_shape *sh, Dims *d) {
+  if (!sh) return MOE_ERR_NULL;
+  if (sh->T < 0 || sh->H < 1 || sh->k < 1 || sh->E < 1 || sh->R < 1) return MOE_ERR_SHAPE;
+  if (sh->E > MOE_MAX_EXPERTS || sh->E % sh->R != 0) return MOE_ERR_SHAPE;
+  if (sh->dtype != MOE_DTYPE_BF16 && sh->dtype != MOE_DTYPE_F32) return MOE_ERR_SHAPE;
+  if (sh->schedule != MOE_SCHEDULE_AUTO && sh->schedule != MOE_SCHEDULE_PREFILL &&
+      sh->schedule != MOE_SCHEDULE_DECODE)
+    return MOE_ERR_SHAPE;
+  if (sh->reserved != 0 || sh->region_stride_rows < 0) return MOE_ERR_SHAPE;
+  const int64_t N = (int64_t)sh->T * sh->k;
+  if (sh->schedule == MOE_SCHEDULE_DECODE && N > MOE_DECODE_MAX_BRANCHES) return MOE_ERR_SHAPE;
+  const int64_t row_bytes = (int64_t)sh->H * elem_bytes(sh->dtype);
+  if (row_bytes % 16 != 0) return MOE_ERR_ALIGN;
+  if (N > INT32_MAX) return MOE_ERR_OVERFLOW;
+  if (sh->region_stride_rows > 0 && (sh->region_stride_rows > INT32_MAX ||
+                                     (int64_t)sh->R * sh->region_stride_rows > INT32_MAX))
+    return MOE_ERR_OVERFLOW;
+  // one workgroup per (token, 16-byte-column chunk): the grid must fit in 31 bits even for 64-lane chunks
+  if ((int64_t)sh->T * ((row_bytes / 16 + 63) / 64) > INT32_MAX) return MOE_ERR_OVERFLOW;
+  if (d) {
+    d->T = sh->T;
+    d->H = sh->H;
+    d->k = sh->k;
+    d->E = sh->E;
+    d->R = sh->R;
+    d->Er = sh->E / sh->R;
+    d->N = (int32_t)N;
+    d->H16 = (int32_t)(row_bytes / 16);
+    d->dtype = sh->dtype;
+    d->stride = sh->region_stride_rows;
+  }
+  return MOE_OK;
+}
+
+int resolve(const moe_shape *sh) {
+  if (sh->schedule != MOE_SCHEDULE_AUTO) return sh->schedule;
+  return (int64_t)sh->T * sh->k <= MOE_AUTO_DECODE_MAX_BRANCHES ? MOE_SCHEDULE_DECODE : MOE_SCHEDULE_PREFILL;
+}
+
+size_t workspace_need(const moe_shape *sh) {
+  const int64_t N = (int64_t)sh->T * sh->k;
+  const size_t b = (size_t)plan_tile_count(N) * (size_t)(sh->E + 1) * sizeof(int32_t);
+  return (b + 255) / 256 * 256;
+}
+
+// Pointer checks for the plan tables that a call WRITES (need_tables) or only reads row_map from.
+int check_plan(const moe_plan_t *pl, bool need_tables, PlanView *v) {
+  if (!pl) return MOE_ERR_NULL;
+  if (!pl->row_map) return MOE_ERR_NULL;
+  if (need_tables && (!pl->expert_count || !pl->rank_count || !pl->expert_offset || !pl->region_base || !pl->status))
+    return MOE_ERR_NULL;
+  if (!aligned16(pl->row_map) || (pl->send_idx && !aligned16(pl->send_idx))) return MOE_ERR_ALIGN;
+  if (need_tables && (!aligned16(pl->expert_count) || !aligned16(pl->rank_count) || !aligned16(pl->expert_offset) ||
+                      !aligned16(pl->region_base) || !aligned16(pl->status)))
+    return MOE_ERR_ALIGN;
+  v->expert_count = pl->expert_count;
+  v->rank_count = pl->rank_count;
+  v->expert_offset = pl->expert_offset;
+  v->region_base = pl->region_base;
+  v->send_idx = pl->send_idx;
+  v->row_map = pl->row_map;
+  v->status = pl->status;
+  return MOE_OK;
+}
+
+int launch_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+int moe_workspace_bytes(const moe_shape *shape, size_t *out_bytes) {
+  if (!out_bytes) return MOE_ERR_NULL;
+  const int rc = check_shape(shape, nullptr);
+  if (rc != MOE_OK) return rc;
+  *out_bytes = workspace_need(shape);
+  return MOE_OK;
+}
+
+int moe_window_rows(const moe_shape *shape, int64_t *out_rows) {
+  if (!out_rows) return MOE_ERR_NULL;
+  const int rc = check_shape(shape, nullptr);
+  if (rc != MOE_OK) return rc;
+  *out_rows = shape->region_stride_rows > 0 ? (int64_t)shape->R * shape->region_stride_rows
+                                            : (int64_t)shape->T * shape->k;
+  return MOE_OK;
+}
+
+int moe_resolve_schedule(const moe_shape *shape, int32_t *out_schedule) {
+  if (!out_schedule) return MOE_ERR_NULL;
+  const int rc = check_shape(shape, nullptr);
+  if (rc != MOE_OK) return rc;
+  *out_schedule = resolve(shape);
+  return MOE_OK;
+}
+
+int moe_plan(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream) {
+  Dims d;
+  PlanView v;
+  int rc = check_shape(shape, &d);
+  if (rc != MOE_OK) return rc;
+  if (!plan) return MOE_ERR_NULL;
+  if (d.T > 0 && !topk_idx) return MOE_ERR_NULL;
+  rc = check_plan(plan, true, &v);
+  if (rc != MOE_OK) return rc;
+  if (!aligned16(topk_idx)) return MOE_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  if (d.T == 0) {
+    return launch_status(launch_plan_empty(d, v, s));
+  }
+  if (!plan->workspace || plan->workspace_bytes < workspace_need(shape)) return MOE_ERR_WORKSPACE;
+  if (!aligned16(plan->workspace)) return MOE_ERR_ALIGN;
+  return launch_status(launch_plan(d, topk_idx, v, (int32_t *)plan->workspace, s));
+}
+
+int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx, moe_plan_t *plan, void *window,
+                 void *stream) {
+  Dims d;
+  PlanView v;
+  int rc = check_shape(shape, &d);
+  if (rc != MOE_OK) return rc;
+  const bool decode = resolve(shape) == MOE_SCHEDULE_DECODE;
+  if (!plan) return MOE_ERR_NULL;
+  if (d.T > 0 && (!x || !window || (decode && !topk_idx))) return MOE_ERR_NULL;
+  rc = check_plan(plan, decode, &v);
+  if (rc != MOE_OK) return rc;
+  if (!aligned16(x) || !aligned16(window) || (decode && !aligned16(topk_idx))) return MOE_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  if (d.T == 0) {
+    return decode ? launch_status(launch_plan_empty(d, v, s)) : MOE_OK;
+  }
+  return launch_status(decode ? launch_decode_dispatch(d, x, topk_idx, v, window, s)
+                              : launch_dispatch(d, x, v, window, s));
+}
+
+int moe_combine(const moe_shape *shape, const void *expert_out, const float *topk_w, const moe_plan_t *plan,
+                void *y, void *stream) {
+  Dims d;
+  PlanView v;
+  int rc = check_shape(shape, &d);
+  if (rc != MOE_OK) return rc;
+  if (!plan) return MOE_ERR_NULL;
+  if (d.T > 0 && (!expert_out || !topk_w || !y)) return MOE_ERR_NULL;
+  rc = check_plan(plan, false, &v);
+  if (rc != MOE_OK) return rc;
+  if (!aligned16(expert_out) || !aligned16(topk_w) || !aligned16(y)) return MOE_ERR_ALIGN;
+  if (d.T == 0) return MOE_OK;
+  return launch_status(launch_combine(d, expert_out, topk_w, v, y, (hipStream_t)stream));
+}
+
+const char *moe_strerror(int status) {
+  switch (status) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_NULL: return "a required pointer is NULL";
+    case MOE_ERR_SHAPE: return "bad shape, dtype or schedule";
+    case MOE_ERR_ALIGN: return "row bytes or a device pointer not 16-byte aligned";
+    case MOE_ERR_OVERFLOW: return "branch or window row count exceeds int32";
+    case MOE_ERR_WORKSPACE: return "plan workspace missing or too small";
+    case MOE_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

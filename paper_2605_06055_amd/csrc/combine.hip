@@ -1,0 +1,125 @@
+// Combine: direct reading of expert outputs from the windows and local weighted reduction in token
+// order (paper, Section 5.2 "Prefill Combine", Section 5.3 "Decode Combine"; second loop of
+// Algorithms 1 and 2):  Y[t,:] = sum_j W[t,j] * Yexp[row_map[t,j], :].
+//
+// Work unit = (token, 16-byte output column).  A thread fetches its column from up to 8 window rows
+// at once (8 independent 16-byte loads in flight per lane), folds them into fp32 accumulators in
+// ascending j with one fused multiply-add per branch, rounds once and stores 16 bytes.  Every window
+// row is read exactly once and Y is written exactly once, in token order: no un-permute buffer.
+// Row ids and weights are uniform per workgroup and live in scalar registers.
+#include "device_utils.h"
+#include "launch.h"
+#include "moe_rbf.h"
+
+namespace moe_rbf {
+
+#ifndef MOE_COMBINE_BLOCK
+#define MOE_COMBINE_BLOCK 128
+#endif
+
+constexpr int kGather = 8;  // rows fetched together
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// two bf16 packed in a dword -> two floats (exact)
+__device__ __forceinline__ float bf16_lo(unsigned u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned u) { return __uint_as_float(u & 0xffff0000u); }
+// two floats -> two bf16, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  f32x2 f;
+  f.x = lo;
+  f.y = hi;
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
+}
+
+template <int DT>
+struct Acc;
+
+template <>
+struct Acc<MOE_DTYPE_BF16> {
+  float a[8];
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = 0.0f;
+  }
+  __device__ __forceinline__ void fma(float w, u32x4 y) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a[2 * i] = __builtin_fmaf(w, bf16_lo(y[i]), a[2 * i]);
+      a[2 * i + 1] = __builtin_fmaf(w, bf16_hi(y[i]), a[2 * i + 1]);
+    }
+  }
+  __device__ __forceinline__ u32x4 result() const {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = pack_bf16(a[2 * i], a[2 * i + 1]);
+    return r;
+  }
+};
+
+template <>
+struct Acc<MOE_DTYPE_F32> {
+  float a[4];
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = 0.0f;
+  }
+  __device__ __forceinline__ void fma(float w, u32x4 y) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = __builtin_fmaf(w, __uint_as_float(y[i]), a[i]);
+  }
+  __device__ __forceinline__ u32x4 result() const {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = __float_as_uint(a[i]);
+    return r;
+  }
+};
+
+template <int BLOCK, int DT>
+__global__ __launch_bounds__(BLOCK) void combine_rows_kernel(const u32x4 *__restrict__ Yexp,
+                                                             const float *__restrict__ W,
+                                                             const int32_t *__restrict__ row_map,
+                                                             u32x4 *__restrict__ Y, int k, int H16, int chunks) {
+  const int t = blockIdx.x / chunks;
+  const int c = blockIdx.x - t * chunks;
+  const int col = c * BLOCK + threadIdx.x;
+  if (col >= H16) return;
+  const int32_t *rows = row_map + (size_t)t * k;
+  const float *w = W + (size_t)t * k;
+  Acc<DT> acc;
+  acc.zero();
+  for (int j0 = 0; j0 < k; j0 += kGather) {
+    int row[kGather];
+    float wj[kGather];
+    u32x4 y[kGather];
+#pragma unroll
+    for (int u = 0; u < kGather; ++u) {
+      const bool in = j0 + u < k;
+      row[u] = in ? uniform(rows[j0 + u]) : -1;
+      wj[u] = in ? __uint_as_float(uniform(__float_as_uint(w[j0 + u]))) : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kGather; ++u)
+      y[u] = row[u] >= 0 ? load_stream(Yexp + (size_t)row[u] * (size_t)H16 + col) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < kGather; ++u)
+      if (row[u] >= 0) acc.fma(wj[u], y[u]);
+  }
+  store_stream(Y + (size_t)t * (size_t)H16 + col, acc.result());
+}
+
+hipError_t launch_combine(const Dims &d, const void *expert_out, const float *W, const PlanView &p, void *y,
+                          hipStream_t s) {
+  constexpr int B = MOE_COMBINE_BLOCK;
+  const int chunks = (d.H16 + B - 1) / B;
+  const dim3 grid((unsigned)d.T * (unsigned)chunks);
+  if (d.dtype == MOE_DTYPE_BF16)
+    return launch(combine_rows_kernel<B, MOE_DTYPE_BF16>, grid, dim3(B), 0, s, (const u32x4 *)expert_out, W,
+                  (const int32_t *)p.row_map, (u32x4 *)y, d.k, d.H16, chunks);
+  return launch(combine_rows_kernel<B, MOE_DTYPE_F32>, grid, dim3(B), 0, s, (const u32x4 *)expert_out, W,
+                (const int32_t *)p.row_map, (u32x4 *)y, d.k, d.H16, chunks);
+}
+
+}  // namespace moe_rbf

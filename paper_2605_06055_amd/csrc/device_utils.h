@@ -1,0 +1,73 @@
+// Device-side helpers for the gfx950 kernels: 128-bit vector type, wave64 primitives.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe_rbf {
+
+// 16-byte payload unit: one global_load/store_dwordx4 per lane.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ int lane_id() {
+  return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
+// Force a block-uniform value into a scalar register.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Number of bits needed to tell ids 0..E-1 apart.
+__host__ __device__ inline int id_bits(int E) {
+  int b = 0;
+  while ((1 << b) < E) ++b;
+  return b;
+}
+
+// For each lane with `valid`, the 64-bit mask of valid lanes in the wave that hold the same id.
+// One ballot per id bit narrows the peer set.
+__device__ __forceinline__ unsigned long long match_any(int id, bool valid, int bits) {
+  unsigned long long mask = __ballot(valid);
+  for (int b = 0; b < bits; ++b) {
+    const bool bit = (id >> b) & 1;
+    const unsigned long long m = __ballot(valid && bit);
+    mask &= bit ? m : ~m;
+  }
+  return mask;
+}
+
+// Inclusive prefix sum across the 64 lanes of a wave.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const int up = __shfl_up(v, d, kWave);
+    if (lane >= d) v += up;
+  }
+  return v;
+}
+
+// Exclusive prefix sum of total[0..E) into g[0..E], g[E] = grand total; executed by ONE wave
+// (all 64 lanes of it must call).  Each lane owns a run of consecutive experts.
+__device__ __forceinline__ void wave_exclusive_scan_lds(const int *total, int *g, int E) {
+  const int lane = lane_id();
+  const int per = (E + kWave - 1) / kWave;
+  const int b = lane * per;
+  int sum = 0;
+  for (int x = 0; x < per; ++x)
+    if (b + x < E) sum += total[b + x];
+  const int incl = wave_inclusive_scan(sum);
+  int run = incl - sum;
+  for (int x = 0; x < per; ++x)
+    if (b + x < E) {
+      g[b + x] = run;
+      run += total[b + x];
+    }
+  if (lane == kWave - 1) g[E] = incl;
+}
+
+// Streaming 16-byte accesses: the payload is touched once by these kernels.
+__device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void store_stream(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+
+}  // namespace moe_rbf

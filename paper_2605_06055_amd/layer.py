@@ -1,0 +1,74 @@
+"""Device buffers of one MoE layer's dispatch/combine plus the three calls in order.
+
+Memory plumbing only: torch allocates the tensors and provides the stream; every step of the
+path runs in the HIP library through the binding.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as B
+
+
+def to_device(a: np.ndarray, device="cuda"):
+    """numpy -> torch on the GPU; uint16 arrays are bf16 bit patterns."""
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def to_host(t) -> np.ndarray:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+class MoeLayer:
+    """Buffers for shape (T,H,k,E,R): plan state, window, expert_out, Y."""
+
+    def __init__(self, T, H, k, E, R, dtype=B.MOE_DTYPE_BF16, schedule=B.MOE_SCHEDULE_AUTO,
+                 region_stride_rows=0, device="cuda", separate_expert_out=True):
+        import torch
+        self.shape = B.MoeShape(T=T, H=H, k=k, E=E, R=R, dtype=dtype, schedule=schedule, reserved=0,
+                                region_stride_rows=region_stride_rows)
+        self.torch_dtype = torch.bfloat16 if dtype == B.MOE_DTYPE_BF16 else torch.float32
+        self.rows = B.moe_window_rows(self.shape)
+        self.schedule = B.moe_resolve_schedule(self.shape)
+        self.plan = B.MoePlan(self.shape, device=device)
+        self._plan_struct = self.plan.struct()
+        self.window = torch.empty((max(self.rows, 1), H), dtype=self.torch_dtype, device=device)
+        self.expert_out = (torch.empty_like(self.window) if separate_expert_out else self.window)
+        self.y = torch.empty((max(T, 1), H), dtype=self.torch_dtype, device=device)
+
+    def dispatch(self, x, topk_idx, stream=None):
+        """Plan (prefill schedule only) + dispatch."""
+        if self.schedule == B.MOE_SCHEDULE_PREFILL:
+            B.moe_plan(self.shape, topk_idx, self._plan_struct, stream)
+        B.moe_dispatch(self.shape, x, topk_idx, self._plan_struct, self.window, stream)
+
+    def combine(self, topk_w, stream=None):
+        B.moe_combine(self.shape, self.expert_out, topk_w, self._plan_struct, self.y, stream)
+
+    def standin_expert(self, topk_idx, scale):
+        """Stand-in for the expert FFNs, outside the library: every placed row times its expert's
+        scalar, rounded to storage (torch ops; not part of the measured path)."""
+        import torch
+        E = self.shape.E
+        n = int(self.plan.expert_offset[E].item()) if self.shape.region_stride_rows == 0 else self.rows
+        if n == 0:
+            return
+        # expert id of every window row from the offsets (rows past an expert's block keep scale 0)
+        off = self.plan.expert_offset[:E].long()
+        cnt = self.plan.expert_count.long()
+        row_scale = torch.zeros(self.rows, dtype=torch.float32, device=self.window.device)
+        ids = torch.repeat_interleave(torch.arange(E, device=off.device), cnt)
+        pos = torch.repeat_interleave(off, cnt) + (torch.arange(ids.numel(), device=off.device)
+                                                   - torch.repeat_interleave(torch.cumsum(cnt, 0) - cnt, cnt))
+        keep = pos < self.rows
+        row_scale[pos[keep]] = scale[ids[keep]]
+        step = max(1, (1 << 27) // self.shape.H)
+        for r0 in range(0, self.rows, step):
+            r1 = min(self.rows, r0 + step)
+            self.expert_out[r0:r1] = (self.window[r0:r1].float() * row_scale[r0:r1, None]).to(self.torch_dtype)

@@ -1,0 +1,141 @@
+"""Host-side behaviour of the C-ABI library that needs no GPU: it loads, exports every symbol the
+header declares, and returns each documented error code from argument validation alone."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_06055_amd as moe
+from paper_2605_06055_amd.binding import _PlanStruct
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "moe_rbf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = moe.load_library()
+    names = declared_symbols()
+    assert {"moe_plan", "moe_dispatch", "moe_combine", "moe_workspace_bytes", "moe_window_rows",
+            "moe_resolve_schedule", "moe_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def shape(**kw):
+    base = dict(T=64, H=256, k=4, E=16, R=4, dtype=moe.MOE_DTYPE_BF16, schedule=moe.MOE_SCHEDULE_AUTO,
+                reserved=0, region_stride_rows=0)
+    base.update(kw)
+    return moe.MoeShape(**base)
+
+
+def code(fn, *a):
+    with pytest.raises(moe.MoeError) as ei:
+        fn(*a)
+    return ei.value.code
+
+
+def test_sizes_and_schedule():
+    s = shape()
+    assert moe.moe_window_rows(s) == 64 * 4
+    assert moe.moe_window_rows(shape(region_stride_rows=100)) == 400
+    assert moe.moe_workspace_bytes(s) % 256 == 0 and moe.moe_workspace_bytes(s) >= (16 + 1) * 4
+    assert moe.moe_resolve_schedule(s) == moe.MOE_SCHEDULE_DECODE
+    assert moe.moe_resolve_schedule(shape(T=513)) == moe.MOE_SCHEDULE_PREFILL       # 2052 branches
+    assert moe.moe_resolve_schedule(shape(T=512)) == moe.MOE_SCHEDULE_DECODE        # 2048 branches
+    assert moe.moe_resolve_schedule(shape(schedule=moe.MOE_SCHEDULE_PREFILL)) == moe.MOE_SCHEDULE_PREFILL
+    big = shape(T=32768, H=4096, k=8, E=128, R=16)
+    assert moe.moe_window_rows(big) * 4096 * 2 == 2 ** 31
+    assert moe.moe_workspace_bytes(big) >= 256 * 129 * 4
+
+
+@pytest.mark.parametrize("kw", [dict(T=-1), dict(H=0), dict(k=0), dict(E=0), dict(R=0), dict(E=10, R=4),
+                                dict(E=2048, R=4), dict(dtype=2), dict(schedule=3), dict(reserved=1),
+                                dict(region_stride_rows=-1),
+                                dict(T=2000, k=8, schedule=moe.MOE_SCHEDULE_DECODE)])
+def test_bad_shape(kw):
+    assert code(moe.moe_window_rows, shape(**kw)) == -2
+    assert code(moe.moe_workspace_bytes, shape(**kw)) == -2
+
+
+def test_k_larger_than_E_is_legal():
+    assert moe.moe_window_rows(shape(k=40, E=16, R=4)) == 64 * 40
+
+
+def test_row_alignment():
+    assert code(moe.moe_window_rows, shape(H=100)) == -3                # 200 B rows
+    assert code(moe.moe_window_rows, shape(H=6, dtype=moe.MOE_DTYPE_F32)) == -3
+    assert moe.moe_window_rows(shape(H=8)) == 256                        # 16 B rows are the minimum
+    assert moe.moe_window_rows(shape(H=4, dtype=moe.MOE_DTYPE_F32)) == 256
+
+
+def test_overflow():
+    assert code(moe.moe_window_rows, shape(T=2 ** 30, k=8)) == -4
+    assert code(moe.moe_window_rows, shape(region_stride_rows=2 ** 30)) == -4
+    assert code(moe.moe_window_rows, shape(T=2 ** 26, k=1, H=2 ** 20)) == -4      # grid would not fit
+
+
+def fake_plan(**kw):
+    """Plan struct with fake (never dereferenced) 16-byte aligned device addresses."""
+    vals = dict(expert_count=0x1000, rank_count=0x2000, expert_offset=0x3000, region_base=0x4000,
+                send_idx=0x5000, row_map=0x6000, status=0x7000, workspace=0x8000, workspace_bytes=1 << 20)
+    vals.update(kw)
+    return _PlanStruct(**vals)
+
+
+PRE = dict(schedule=moe.MOE_SCHEDULE_PREFILL)
+
+
+def test_null_pointers():
+    s = shape(**PRE)
+    assert code(moe.moe_plan, s, None, fake_plan(), 0) == -1
+    assert code(moe.moe_plan, s, 0x100, fake_plan(row_map=None), 0) == -1
+    assert code(moe.moe_plan, s, 0x100, fake_plan(expert_count=None), 0) == -1
+    assert code(moe.moe_plan, s, 0x100, fake_plan(status=None), 0) == -1
+    assert code(moe.moe_dispatch, s, None, None, fake_plan(), 0x100, 0) == -1
+    assert code(moe.moe_dispatch, s, 0x100, None, fake_plan(), None, 0) == -1
+    assert code(moe.moe_dispatch, shape(), 0x100, None, fake_plan(), 0x200, 0) == -1     # decode needs ids
+    assert code(moe.moe_dispatch, shape(), 0x100, 0x300, fake_plan(rank_count=None), 0x200, 0) == -1
+    assert code(moe.moe_combine, s, None, 0x100, fake_plan(), 0x200, 0) == -1
+    assert code(moe.moe_combine, s, 0x100, None, fake_plan(), 0x200, 0) == -1
+    assert code(moe.moe_combine, s, 0x100, 0x200, fake_plan(), None, 0) == -1
+    assert code(moe.moe_combine, s, 0x100, 0x200, fake_plan(row_map=None), 0x300, 0) == -1
+    lib = moe.load_library()
+    assert lib.moe_plan(ctypes.byref(s), 0x100, None, None) == -1
+    assert lib.moe_window_rows(None, ctypes.byref(ctypes.c_int64())) == -1
+    assert lib.moe_window_rows(ctypes.byref(s), None) == -1
+
+
+def test_pointer_alignment():
+    s = shape(**PRE)
+    assert code(moe.moe_plan, s, 0x104, fake_plan(), 0) == -3
+    assert code(moe.moe_plan, s, 0x100, fake_plan(row_map=0x6004), 0) == -3
+    assert code(moe.moe_plan, s, 0x100, fake_plan(send_idx=0x5008), 0) == -3
+    assert code(moe.moe_plan, s, 0x100, fake_plan(workspace=0x8001), 0) == -3
+    assert code(moe.moe_dispatch, s, 0x108, None, fake_plan(), 0x200, 0) == -3
+    assert code(moe.moe_dispatch, s, 0x100, None, fake_plan(), 0x202, 0) == -3
+    assert code(moe.moe_combine, s, 0x100, 0x204, fake_plan(), 0x300, 0) == -3
+    assert code(moe.moe_combine, s, 0x100, 0x200, fake_plan(), 0x308, 0) == -3
+
+
+def test_workspace():
+    s = shape(**PRE)
+    need = moe.moe_workspace_bytes(s)
+    assert code(moe.moe_plan, s, 0x100, fake_plan(workspace=None), 0) == -5
+    assert code(moe.moe_plan, s, 0x100, fake_plan(workspace_bytes=need - 1), 0) == -5
+
+
+def test_empty_prefill_dispatch_and_combine_are_noops():
+    s = shape(T=0, **PRE)
+    moe.moe_dispatch(s, None, None, fake_plan(), None, 0)          # returns OK without any launch
+    moe.moe_combine(s, None, None, fake_plan(), None, 0)
+
+
+def test_strerror():
+    texts = {moe.moe_strerror(c) for c in range(0, -7, -1)}
+    assert len(texts) == 7 and moe.moe_strerror(-99) == "unknown status"

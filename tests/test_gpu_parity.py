@@ -1,0 +1,243 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C-ABI.
+
+Bar: counts, offsets, small offsets, row map and every dispatched window byte bit-exact;
+combine within 1 bf16 ulp (fp32 storage: bit-exact up to the same bound in fp32 ulps), with the
+fp32 accumulate / ascending-j / fused-multiply-add decision taken in the same precision on both sides.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def moe():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2605_06055_amd as m
+    m.load_library()          # raises if the HIP library was not built: there is no fallback
+    return m
+
+
+def ordered_bits(a: np.ndarray) -> np.ndarray:
+    """Monotone integer image of bf16 (uint16) or fp32 bit patterns."""
+    if a.dtype == np.uint16:
+        b = a.astype(np.int64)
+        return np.where(b & 0x8000, 0x8000 - b, b)
+    b = a.view(np.uint32).astype(np.int64)
+    return np.where(b & 0x80000000, 0x80000000 - b, b)
+
+
+def max_ulp(a, b):
+    return int(np.abs(ordered_bits(a) - ordered_bits(b)).max()) if a.size else 0
+
+
+SENTINEL = {np.dtype(np.uint16): 0x7B7B, np.dtype(np.float32): np.float32(-1234.5)}
+
+
+def run_case(moe, X, K, W, scale, E, R, schedule, stride=0, label=""):
+    """One full layer on the GPU through the C-ABI, compared with the oracle.  Returns GPU outputs."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    T, H = X.shape
+    k = K.shape[1]
+    dtype = moe.MOE_DTYPE_BF16 if X.dtype == np.uint16 else moe.MOE_DTYPE_F32
+    print(f"[case] {label} T={T} H={H} k={k} E={E} R={R} dtype={dtype} schedule={schedule} stride={stride}",
+          flush=True)
+    ref = oracle.plan(K, E, R, stride)
+    layer = MoeLayer(T, H, k, E, R, dtype=dtype, schedule=schedule, region_stride_rows=stride)
+    fill = SENTINEL[X.dtype]
+    layer.window.copy_(to_device(np.full(tuple(layer.window.shape), fill, X.dtype)))
+    for t in (layer.plan.expert_count, layer.plan.rank_count, layer.plan.expert_offset, layer.plan.region_base,
+              layer.plan.send_idx, layer.plan.row_map, layer.plan.status):
+        t.fill_(-7)
+    xd = to_device(X) if T else torch.empty((1, H), dtype=layer.torch_dtype, device="cuda")
+    kd = to_device(K) if T else torch.empty((1, k), dtype=torch.int32, device="cuda")
+    wd = to_device(W) if T else torch.empty((1, k), dtype=torch.float32, device="cuda")
+    if layer.schedule == moe.MOE_SCHEDULE_PREFILL:
+        # the row map is checked on the host before any payload is moved with it
+        moe.moe_plan(layer.shape, kd, layer.plan)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(layer.plan.row_map)[:T * k].reshape(T, k), ref.row_map), "row_map (plan only)"
+    layer.dispatch(xd, kd)
+    torch.cuda.synchronize()
+
+    p = layer.plan
+    N = T * k
+    got = dict(c_exp=to_host(p.expert_count), c_rank=to_host(p.rank_count), expert_offset=to_host(p.expert_offset),
+               region_base=to_host(p.region_base), s=to_host(p.send_idx)[:N].reshape(T, k),
+               row_map=to_host(p.row_map)[:N].reshape(T, k), status=to_host(p.status)[:2])
+    assert np.array_equal(got["c_exp"], ref.c_exp), "expert_count"
+    assert np.array_equal(got["c_rank"], ref.c_rank), "rank_count"
+    assert np.array_equal(got["expert_offset"], ref.expert_offset), "expert_offset"
+    assert np.array_equal(got["region_base"], ref.region_base), "region_base"
+    assert np.array_equal(got["s"], ref.s), "send_idx"
+    assert np.array_equal(got["row_map"], ref.row_map), "row_map"
+    assert np.array_equal(got["status"], ref.status), "status"
+
+    rows = moe.moe_window_rows(layer.shape)
+    assert rows == (ref.window_rows if stride == 0 else R * stride)
+    ref_window = oracle.dispatch(X, ref.row_map, rows, fill=fill)
+    got_window = to_host(layer.window)[:rows]
+    assert got_window.tobytes() == ref_window.tobytes(), "window bytes"
+
+    # expert stand-in computed once on the CPU from the (bit-identical) window and used by both sides
+    Yexp = oracle.expert_standin(ref_window, K, ref.row_map, scale)
+    if rows:
+        layer.expert_out[:rows].copy_(to_device(Yexp))
+    layer.y.copy_(to_device(np.full(tuple(layer.y.shape), fill, X.dtype)))
+    layer.combine(wd)
+    torch.cuda.synchronize()
+    got_Y = to_host(layer.y)[:T]
+    ref_Y = oracle.combine(Yexp, W, ref.row_map)
+    nan_ref = np.isnan(wl.bf16_bits_to_f32(ref_Y)) if ref_Y.dtype == np.uint16 else np.isnan(ref_Y)
+    nan_got = np.isnan(wl.bf16_bits_to_f32(got_Y)) if got_Y.dtype == np.uint16 else np.isnan(got_Y)
+    assert np.array_equal(nan_ref, nan_got)
+    d = max_ulp(got_Y[~nan_ref], ref_Y[~nan_ref])
+    exact = np.count_nonzero(got_Y != ref_Y)
+    print(f"       combine: max ulp distance {d}, {exact} of {got_Y.size} elements differ", flush=True)
+    assert d <= 1, f"combine differs from the oracle by {d} ulp"
+    got["window"], got["Y"] = got_window, got_Y
+    return got
+
+
+def run_workload(moe, cfg, schedule, stride=0):
+    w = wl.make(cfg)
+    return run_case(moe, w.X, w.K, w.W, w.scale, cfg.E, cfg.R, schedule, stride, label=cfg.name)
+
+
+# --------------------------------------------------------------------------- the named configurations
+
+def test_tiny_both_schedules(moe):
+    a = run_workload(moe, wl.CONFIGS["tiny"], moe.MOE_SCHEDULE_PREFILL)
+    b = run_workload(moe, wl.CONFIGS["tiny"], moe.MOE_SCHEDULE_DECODE)
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_decode_config_both_schedules(moe):
+    cfg = wl.CONFIGS["decode"]
+    a = run_workload(moe, cfg, moe.MOE_SCHEDULE_AUTO)          # resolves to the fused decode schedule
+    b = run_workload(moe, cfg, moe.MOE_SCHEDULE_PREFILL)
+    for key in a:
+        assert a[key].tobytes() == b[key].tobytes(), key        # schedules give identical values
+
+
+@pytest.mark.parametrize("name", ["prefill", "skewed", "wide"])
+def test_full_size_prefill_configs(moe, name):
+    """Full benchmark sizes, in the launch configuration bench.py times, compared in full."""
+    cfg = wl.CONFIGS[name]
+    got = run_workload(moe, cfg, moe.MOE_SCHEDULE_AUTO)
+    if name == "skewed":
+        assert got["c_exp"].max() > 10 * cfg.N / cfg.E          # the hot experts really are hot
+
+
+# --------------------------------------------------------------------------- several tiles, ragged tails
+
+@pytest.mark.parametrize("T,H,k,E,R", [
+    (777, 7168, 8, 256, 32),     # 6216 branches: 7 plan tiles, ragged last tile and last wave round
+    (1500, 4096, 6, 96, 12),     # E not a power of two, k not a power of two
+    (333, 1032, 3, 1024, 64),    # E at the limit, rows of 129 vectors (ragged chunk)
+    (2049, 512, 1, 4, 1),        # k = 1, one region
+    (129, 8, 16, 16, 16),        # 16-byte rows, E = R
+])
+@pytest.mark.parametrize("dtype", [wl.DTYPE_BF16, wl.DTYPE_F32])
+def test_ragged_shapes(moe, T, H, k, E, R, dtype):
+    if dtype == wl.DTYPE_F32:
+        H = max(4, H // 2)
+    cfg = wl.Config("ragged", T=T, H=H, k=k, E=E, R=R, dtype=dtype, seed=T)
+    run_workload(moe, cfg, moe.MOE_SCHEDULE_PREFILL)
+
+
+@pytest.mark.parametrize("T,H,k,E,R", [(1, 7168, 8, 256, 32), (37, 4096, 8, 128, 16), (255, 264, 8, 64, 8),
+                                       (1024, 64, 8, 256, 32), (100, 2048, 20, 24, 3)])
+def test_decode_schedule_matches_prefill(moe, T, H, k, E, R):
+    cfg = wl.Config("dec", T=T, H=H, k=k, E=E, R=R, seed=T + 1)
+    a = run_workload(moe, cfg, moe.MOE_SCHEDULE_DECODE)
+    b = run_workload(moe, cfg, moe.MOE_SCHEDULE_PREFILL)
+    for key in a:
+        assert a[key].tobytes() == b[key].tobytes(), key
+
+
+# --------------------------------------------------------------------------- degenerate routing
+
+def _case(moe, K, E, R, schedule, H=64, stride=0, dtype=np.uint16, seed=0, label=""):
+    rng = np.random.default_rng(seed)
+    T, k = K.shape
+    Xf = rng.standard_normal((T, H)).astype(np.float32)
+    X = wl.f32_to_bf16_bits(Xf) if dtype == np.uint16 else Xf
+    W = rng.random((T, k)).astype(np.float32)
+    scale = rng.uniform(0.5, 1.5, E).astype(np.float32)
+    return run_case(moe, X, K, W, scale, E, R, schedule, stride, label)
+
+
+@pytest.mark.parametrize("schedule", ["prefill", "decode"])
+def test_edge_cases(moe, schedule):
+    sch = moe.MOE_SCHEDULE_PREFILL if schedule == "prefill" else moe.MOE_SCHEDULE_DECODE
+    rng = np.random.default_rng(11)
+    # no tokens
+    _case(moe, np.zeros((0, 4), np.int32), 8, 2, sch, label="T=0")
+    # one token, one slot
+    _case(moe, np.array([[3]], np.int32), 8, 2, sch, label="T=1,k=1")
+    # every branch to one expert (longest possible stream, maximal atomic contention)
+    _case(moe, np.full((300, 4), 5, np.int32), 8, 4, sch, label="one expert")
+    # duplicates inside a token and k > E
+    _case(moe, wl.random_routing(rng, 90, 12, 5), 5, 5, sch, label="k>E duplicates")
+    # masked slots and out-of-range ids
+    _case(moe, wl.random_routing(rng, 200, 6, 32, p_masked=0.3, p_invalid=0.1), 32, 8, sch, label="masked+invalid")
+    # everything masked
+    _case(moe, np.full((17, 3), -1, np.int32), 4, 2, sch, label="all masked")
+    # E = 1
+    _case(moe, np.zeros((65, 2), np.int32), 1, 1, sch, label="E=1")
+    # fp32 storage with masked slots
+    _case(moe, wl.random_routing(rng, 70, 4, 16, p_masked=0.2), 16, 4, sch, H=36, dtype=np.float32, label="fp32")
+
+
+@pytest.mark.parametrize("schedule", ["prefill", "decode"])
+def test_fixed_stride_windows(moe, schedule):
+    sch = moe.MOE_SCHEDULE_PREFILL if schedule == "prefill" else moe.MOE_SCHEDULE_DECODE
+    rng = np.random.default_rng(12)
+    K = wl.random_routing(rng, 250, 4, 16, distinct=True)
+    tight = oracle.plan(K, 16, 4)
+    roomy = int(tight.c_rank.max()) + 5
+    got = _case(moe, K, 16, 4, sch, stride=roomy, label="stride roomy")
+    assert got["status"][1] == 0
+    tightest = int(np.sort(tight.c_rank)[1])            # some regions overflow
+    got = _case(moe, K, 16, 4, sch, stride=tightest, label="stride overflow")
+    assert got["status"][1] > 0 and (got["row_map"] == -1).sum() == got["status"][1]
+
+
+def test_special_values_in_combine(moe):
+    """Inf, NaN, signed zeros and subnormals travel through dispatch unchanged and through combine as in the oracle."""
+    T, H, k, E, R = 8, 64, 2, 4, 2
+    rng = np.random.default_rng(13)
+    X = rng.integers(0, 2 ** 16, size=(T, H)).astype(np.uint16)         # arbitrary bf16 bit patterns
+    X[0, :8] = [0x7F80, 0xFF80, 0x7FC0, 0x0000, 0x8000, 0x0001, 0x8001, 0x7F7F]
+    K = wl.random_routing(rng, T, k, E, distinct=True)
+    W = rng.standard_normal((T, k)).astype(np.float32)
+    run_case(moe, X, K, W, np.ones(E, np.float32), E, R, moe.MOE_SCHEDULE_PREFILL, label="special values")
+
+
+def test_run_to_run_determinism(moe):
+    cfg = wl.Config("det", T=3000, H=1024, k=8, E=256, R=32, routing="zipf", seed=5)
+    a = run_workload(moe, cfg, moe.MOE_SCHEDULE_PREFILL)
+    b = run_workload(moe, cfg, moe.MOE_SCHEDULE_PREFILL)
+    for key in a:
+        assert a[key].tobytes() == b[key].tobytes(), key
+
+
+def test_identity_expert_round_trip_on_gpu(moe):
+    """Dispatch then combine with the window itself as expert output and weights summing to 1
+    restores the input to within 1 ulp (the spec invariant), here on the GPU path alone."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    cfg = wl.CONFIGS["decode"]
+    w = wl.make(cfg)
+    layer = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, separate_expert_out=False)
+    layer.dispatch(to_device(w.X), to_device(w.K))
+    layer.combine(to_device(w.W))
+    torch.cuda.synchronize()
+    assert max_ulp(to_host(layer.y), w.X) <= 1
