@@ -21,6 +21,9 @@
  *     synchronises: all work is enqueued on the caller's stream and results are
  *     valid once that stream reaches the end of the call's work.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - The shared library does not name a HIP runtime of its own: it binds to the libamdhip64 that the
+ *     process has already loaded with global symbol visibility (e.g. the one PyTorch ships), so the
+ *     caller's streams and device pointers belong to the same runtime as the library's launches.
  *   - moe_shape and moe_plan_t are read on the host during the call only.
  *   - All tensors are row-major and dense.  X, window, expert_out and Y share
  *     `dtype`; K is int32; W is float32; all counts and offsets are int32.
@@ -130,6 +133,10 @@ int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx,
  *   y          : device, [T,H], every row written; must not overlap expert_out. */
 int moe_combine(const moe_shape *shape, const void *expert_out, const float *topk_w, const moe_plan_t *plan,
                 void *y, void *stream);
+
+/* HIP runtime's description of the most recent launch result on the calling thread (diagnostics for
+ * MOE_ERR_LAUNCH; "no error" if the last launch succeeded). */
+const char *moe_last_launch_error(void);
 
 /* Static string for a moe_status value. */
 const char *moe_strerror(int status);

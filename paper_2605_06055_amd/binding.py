@@ -15,7 +15,8 @@ _lib = None
 class MoeError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        super().__init__(f"{where}: {moe_strerror(code)} ({code})")
+        detail = f" [{load_library().moe_last_launch_error().decode()}]" if code == -6 else ""
+        super().__init__(f"{where}: {moe_strerror(code)} ({code}){detail}")
 
 
 class MoeShape(ctypes.Structure):
@@ -37,6 +38,19 @@ def library_path() -> str:
     return os.environ.get("MOE_RBF_LIB", os.path.join(_PKG, "libmoe_rbf.so"))
 
 
+def _bind_hip_runtime() -> None:
+    """libmoe_rbf.so carries no DT_NEEDED on a HIP runtime: it must bind to the ONE runtime of the
+    process, so that the caller's streams and device pointers mean the same thing to it.  With
+    PyTorch that is the libamdhip64 inside the torch wheel (not /opt/rocm's); it is promoted to
+    the global symbol scope before the library is opened."""
+    try:
+        import torch
+        cand = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    except ImportError:
+        cand = ""
+    ctypes.CDLL(cand if os.path.exists(cand) else "libamdhip64.so", mode=ctypes.RTLD_GLOBAL)
+
+
 def load_library():
     """Loads the built HIP library; raises if it has not been built (there is no fallback)."""
     global _lib
@@ -45,6 +59,7 @@ def load_library():
         if not os.path.exists(path):
             raise ImportError(f"{path} not found: build it with `python -m paper_2605_06055_amd.build` "
                               "(or __graft_entry__.build()); this package has no CPU fallback")
+        _bind_hip_runtime()
         lib = ctypes.CDLL(path)
         vp, i32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
         shp, plp = ctypes.POINTER(MoeShape), ctypes.POINTER(_PlanStruct)
@@ -56,6 +71,8 @@ def load_library():
         lib.moe_combine.argtypes = [shp, vp, vp, plp, vp, vp]
         lib.moe_strerror.argtypes = [ctypes.c_int]
         lib.moe_strerror.restype = ctypes.c_char_p
+        lib.moe_last_launch_error.argtypes = []
+        lib.moe_last_launch_error.restype = ctypes.c_char_p
         for f in ("moe_workspace_bytes", "moe_window_rows", "moe_resolve_schedule", "moe_plan", "moe_dispatch",
                   "moe_combine"):
             getattr(lib, f).restype = ctypes.c_int

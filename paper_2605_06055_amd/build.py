@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     # packed-fp32 instruction selection is switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
+    # No DT_NEEDED on a HIP runtime: the library binds to the runtime already loaded in the process
+    # (PyTorch ships its own libamdhip64), so streams and device pointers belong to ONE runtime.
+    "-no-hip-rt",
 ]
 
 

@@ -79,7 +79,12 @@ int check_plan(const moe_plan_t *pl, bool need_tables, PlanView *v) {
   return MOE_OK;
 }
 
-int launch_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH; }
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+int launch_status(hipError_t e) {
+  g_last_hip_error = e;
+  return e == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH;
+}
 
 }  // namespace
 
@@ -163,6 +168,8 @@ int moe_combine(const moe_shape *shape, const void *expert_out, const float *top
   if (d.T == 0) return MOE_OK;
   return launch_status(launch_combine(d, expert_out, topk_w, v, y, (hipStream_t)stream));
 }
+
+const char *moe_last_launch_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 const char *moe_strerror(int status) {
   switch (status) {

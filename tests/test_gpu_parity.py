@@ -80,7 +80,7 @@ def run_case(moe, X, K, W, scale, E, R, schedule, stride=0, label=""):
     assert np.array_equal(got["status"], ref.status), "status"
 
     rows = moe.moe_window_rows(layer.shape)
-    assert rows == (ref.window_rows if stride == 0 else R * stride)
+    assert rows == (T * k if stride == 0 else R * stride) and ref.window_rows <= rows
     ref_window = oracle.dispatch(X, ref.row_map, rows, fill=fill)
     got_window = to_host(layer.window)[:rows]
     assert got_window.tobytes() == ref_window.tobytes(), "window bytes"
