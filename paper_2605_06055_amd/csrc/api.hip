@@ -31,8 +31,8 @@ int check_shape(const moe_shape *sh, Dims *d) {
   if (sh->region_stride_rows > 0 && (sh->region_stride_rows > INT32_MAX ||
                                      (int64_t)sh->R * sh->region_stride_rows > INT32_MAX))
     return MOE_ERR_OVERFLOW;
-  // one workgroup per (token, 16-byte-column chunk): the grid must fit in 31 bits even for 64-lane chunks
-  if ((int64_t)sh->T * ((row_bytes / 16 + 63) / 64) > INT32_MAX) return MOE_ERR_OVERFLOW;
+  // one workgroup per (token, 64-lane column chunk) or per (branch, 1/8 of a row): grids must fit in 31 bits
+  if ((int64_t)sh->T * ((row_bytes / 16 + 63) / 64) > INT32_MAX || N * 8 > INT32_MAX) return MOE_ERR_OVERFLOW;
   if (d) {
     d->T = sh->T;
     d->H = sh->H;

@@ -16,6 +16,17 @@ namespace moe_rbf {
 #ifndef MOE_COMBINE_BLOCK
 #define MOE_COMBINE_BLOCK 128
 #endif
+#ifndef MOE_COMBINE_SLICES
+#define MOE_COMBINE_SLICES 0
+#endif
+#ifndef MOE_COMBINE_NT
+#define MOE_COMBINE_NT 1
+#endif
+#if MOE_COMBINE_NT
+#define MOE_COMBINE_LOAD(p) load_stream(p)
+#else
+#define MOE_COMBINE_LOAD(p) (*(p))
+#endif
 
 constexpr int kGather = 8;  // rows fetched together
 
@@ -77,49 +88,79 @@ struct Acc<MOE_DTYPE_F32> {
   }
 };
 
-template <int BLOCK, int DT>
+// KFIX > 0: the routing degree is the compile-time constant KFIX (straight-line code, no bounds tests);
+// KFIX == 0: any k, rows taken kGather at a time.
+template <int BLOCK, int DT, int KFIX>
 __global__ __launch_bounds__(BLOCK) void combine_rows_kernel(const u32x4 *__restrict__ Yexp,
                                                              const float *__restrict__ W,
                                                              const int32_t *__restrict__ row_map,
-                                                             u32x4 *__restrict__ Y, int k, int H16, int chunks) {
+                                                             u32x4 *__restrict__ Y, int k_arg, int H16, int chunks) {
+  const int k = KFIX > 0 ? KFIX : k_arg;
   const int t = blockIdx.x / chunks;
   const int c = blockIdx.x - t * chunks;
+#if MOE_COMBINE_SLICES
+  const int slice = (H16 + chunks - 1) / chunks;
+  const int col = c * slice + threadIdx.x;
+  if ((int)threadIdx.x >= slice || col >= H16) return;
+#else
   const int col = c * BLOCK + threadIdx.x;
   if (col >= H16) return;
+#endif
   const int32_t *rows = row_map + (size_t)t * k;
   const float *w = W + (size_t)t * k;
+  const u32x4 *base = Yexp + col;
   Acc<DT> acc;
   acc.zero();
-  for (int j0 = 0; j0 < k; j0 += kGather) {
-    int row[kGather];
-    float wj[kGather];
-    u32x4 y[kGather];
+  constexpr int G = KFIX > 0 ? (KFIX < kGather ? KFIX : kGather) : kGather;
+  for (int j0 = 0; j0 < k; j0 += G) {
+    int row[G];
+    float wj[G];
+    u32x4 y[G];
 #pragma unroll
-    for (int u = 0; u < kGather; ++u) {
-      const bool in = j0 + u < k;
+    for (int u = 0; u < G; ++u) {
+      const bool in = (KFIX > 0 && KFIX % G == 0) || j0 + u < k;
       row[u] = in ? uniform(rows[j0 + u]) : -1;
       wj[u] = in ? __uint_as_float(uniform(__float_as_uint(w[j0 + u]))) : 0.0f;
     }
 #pragma unroll
-    for (int u = 0; u < kGather; ++u)
-      y[u] = row[u] >= 0 ? load_stream(Yexp + (size_t)row[u] * (size_t)H16 + col) : u32x4{0u, 0u, 0u, 0u};
+    for (int u = 0; u < G; ++u)
+      y[u] = row[u] >= 0 ? MOE_COMBINE_LOAD(base + (size_t)row[u] * (size_t)H16) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int u = 0; u < kGather; ++u)
+    for (int u = 0; u < G; ++u)
       if (row[u] >= 0) acc.fma(wj[u], y[u]);
   }
   store_stream(Y + (size_t)t * (size_t)H16 + col, acc.result());
 }
 
+template <int DT>
+static hipError_t launch_combine_dt(const Dims &d, const void *expert_out, const float *W, const PlanView &p, void *y,
+                                    hipStream_t s) {
+  constexpr int B = MOE_COMBINE_BLOCK;
+#if MOE_COMBINE_SLICES
+  const int per = (d.H16 + 7) / 8;                        // 8 slices, more if a slice exceeds the block
+  const int chunks = 8 * ((per + B - 1) / B);
+#else
+  const int chunks = (d.H16 + B - 1) / B;
+#endif
+  const dim3 grid((unsigned)d.T * (unsigned)chunks);
+  auto go = [&](auto kernel) {
+    return launch(kernel, grid, dim3(B), 0, s, (const u32x4 *)expert_out, W, (const int32_t *)p.row_map, (u32x4 *)y,
+                  d.k, d.H16, chunks);
+  };
+  switch (d.k) {
+    case 8: return go(combine_rows_kernel<B, DT, 8>);
+    case 6: return go(combine_rows_kernel<B, DT, 6>);
+    case 4: return go(combine_rows_kernel<B, DT, 4>);
+    case 2: return go(combine_rows_kernel<B, DT, 2>);
+    case 1: return go(combine_rows_kernel<B, DT, 1>);
+    default: return go(combine_rows_kernel<B, DT, 0>);
+  }
+}
+
 hipError_t launch_combine(const Dims &d, const void *expert_out, const float *W, const PlanView &p, void *y,
                           hipStream_t s) {
-  constexpr int B = MOE_COMBINE_BLOCK;
-  const int chunks = (d.H16 + B - 1) / B;
-  const dim3 grid((unsigned)d.T * (unsigned)chunks);
-  if (d.dtype == MOE_DTYPE_BF16)
-    return launch(combine_rows_kernel<B, MOE_DTYPE_BF16>, grid, dim3(B), 0, s, (const u32x4 *)expert_out, W,
-                  (const int32_t *)p.row_map, (u32x4 *)y, d.k, d.H16, chunks);
-  return launch(combine_rows_kernel<B, MOE_DTYPE_F32>, grid, dim3(B), 0, s, (const u32x4 *)expert_out, W,
-                (const int32_t *)p.row_map, (u32x4 *)y, d.k, d.H16, chunks);
+  return d.dtype == MOE_DTYPE_BF16 ? launch_combine_dt<MOE_DTYPE_BF16>(d, expert_out, W, p, y, s)
+                                   : launch_combine_dt<MOE_DTYPE_F32>(d, expert_out, W, p, y, s);
 }
 
 }  // namespace moe_rbf

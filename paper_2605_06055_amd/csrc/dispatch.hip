@@ -8,6 +8,8 @@
 // No reuse exists between workgroups (each row segment is read once), so the order in which
 // workgroups land on the 8 XCDs does not matter for L2.
 //
+// (That token-major fan-out is the decode kernel.  The prefill kernel is organised differently, see
+// dispatch_slices_kernel.)
 // Prefill schedule: the row map comes from moe_plan.
 // Decode schedule : every workgroup rebuilds the plan values it needs from the routing ids in LDS
 //   (histogram of all ids, histogram of the ids before its token, exclusive scan), so counts,
@@ -32,6 +34,18 @@ namespace moe_rbf {
 #ifndef MOE_DECODE_VEC
 #define MOE_DECODE_VEC 1
 #endif
+#ifndef MOE_DISPATCH_NT
+#define MOE_DISPATCH_NT 1
+#endif
+#ifndef MOE_DISPATCH_SLICES
+#define MOE_DISPATCH_SLICES 1
+#endif
+constexpr int kSlices = 8;   // column slices per row = XCDs per device
+#if MOE_DISPATCH_NT
+#define MOE_DISPATCH_STORE(p, v) store_stream(p, v)
+#else
+#define MOE_DISPATCH_STORE(p, v) (*(p) = (v))
+#endif
 
 constexpr int kRowBatch = 8;  // destination rows whose indices are fetched together
 
@@ -50,7 +64,7 @@ __device__ __forceinline__ void scatter_rows(const u32x4 (&v)[V], const int32_t 
 #pragma unroll
       for (int x = 0; x < V; ++x) {
         const int col = col0 + x * BLOCK;
-        if (col < H16) store_stream(dst + col, v[x]);
+        if (col < H16) MOE_DISPATCH_STORE(dst + col, v[x]);
       }
     }
   }
@@ -71,6 +85,34 @@ __global__ __launch_bounds__(BLOCK) void dispatch_rows_kernel(const u32x4 *__res
     v[x] = col < H16 ? load_stream(src + col) : u32x4{0u, 0u, 0u, 0u};
   }
   scatter_rows<BLOCK, V>(v, row_map + (size_t)t * k, k, window, H16, col0);
+}
+
+// Prefill dispatch, XCD-affine column slices.  Work unit = (branch n = t*k+j, column slice c of 8).
+// Workgroup b handles slice c = b % 8 of branch n = b / 8.  Workgroups are handed to the 8 XCDs
+// round-robin, so XCD c only ever touches column slice c: the k re-reads of X[t]'s slice by the k
+// consecutive branches of a token hit in that XCD's L2 (X is fetched from HBM once), every wave issues
+// a single 16-byte store per lane, and the 8 XCDs together lay down whole destination rows.
+// (If the hardware maps workgroups differently the result is unchanged; only the L2 reuse is lost.)
+template <int BLOCK, int J>
+__global__ __launch_bounds__(BLOCK) void dispatch_slices_kernel(const u32x4 *__restrict__ X,
+                                                                const int32_t *__restrict__ row_map,
+                                                                u32x4 *__restrict__ window, int k, int H16, int slice,
+                                                                int nslices) {
+  const int g = blockIdx.x / nslices;
+  const int c = blockIdx.x - g * nslices;
+  const int n = g * J;                       // J consecutive branches of one token (J divides k)
+  int row[J];
+#pragma unroll
+  for (int u = 0; u < J; ++u) row[u] = uniform(row_map[n + u]);
+  const int t = n / k;
+  const int end = min((c + 1) * slice, H16);
+  const u32x4 *src = X + (size_t)t * (size_t)H16;
+  for (int col = c * slice + threadIdx.x; col < end; col += BLOCK) {
+    const u32x4 v = src[col];
+#pragma unroll
+    for (int u = 0; u < J; ++u)
+      if (row[u] >= 0) MOE_DISPATCH_STORE(window + (size_t)row[u] * (size_t)H16 + col, v);
+  }
 }
 
 template <int BLOCK, int V>
@@ -147,6 +189,28 @@ static hipError_t launch_dispatch_cfg(const Dims &d, const void *x, const PlanVi
 
 hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void *window, hipStream_t s) {
   constexpr int B = MOE_DISPATCH_BLOCK;
+#if MOE_DISPATCH_SLICES
+  {
+    // one wave per slice when a slice is <= 64 vectors; several branches of a token per workgroup when
+    // a slice is short, so that the workgroup count stays within what the dispatcher sustains
+    const int slice = (d.H16 + kSlices - 1) / kSlices;
+    const int slice_bytes = slice * 16;
+    const int want = slice <= 64 ? 4096 : 1792;
+    int J = 1;
+    while (J < 8 && J * slice_bytes < want && d.k % (2 * J) == 0) J *= 2;
+    const dim3 grid((unsigned)(d.N / J) * (unsigned)kSlices);
+    const u32x4 *xs = (const u32x4 *)x;
+    u32x4 *win = (u32x4 *)window;
+#define MOE_GO(B_, J_) \
+  return launch(dispatch_slices_kernel<B_, J_>, grid, dim3(B_), 0, s, xs, (const int32_t *)p.row_map, win, d.k, d.H16, \
+                slice, kSlices)
+    if (J == 1) MOE_GO(128, 1);
+    if (J == 2) MOE_GO(128, 2);
+    if (J == 4) MOE_GO(128, 4);
+    MOE_GO(128, 8);
+#undef MOE_GO
+  }
+#endif
 #if MOE_DISPATCH_VEC > 0
   return launch_dispatch_cfg<B, MOE_DISPATCH_VEC>(d, x, p, window, s);
 #else
