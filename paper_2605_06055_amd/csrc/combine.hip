@@ -125,11 +125,25 @@ __global__ __launch_bounds__(BLOCK) void combine_rows_kernel(const u32x4 *__rest
 #pragma unroll
     for (int u = 0; u < G; ++u)
       y[u] = row[u] >= 0 ? MOE_COMBINE_LOAD(base + (size_t)row[u] * (size_t)H16) : u32x4{0u, 0u, 0u, 0u};
+#if MOE_EXP_NOMATH
+    u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < G; ++u) z ^= y[u];
+    acc.a[0] += __uint_as_float(z.x ^ z.y ^ z.z ^ z.w) * wj[0];
+#else
 #pragma unroll
     for (int u = 0; u < G; ++u)
       if (row[u] >= 0) acc.fma(wj[u], y[u]);
+#endif
   }
+#if MOE_EXP_NOSTORE
+  if (acc.a[0] == 1.2345f)
+#endif
+#ifdef MOE_EXP_STORE_FLAGS
+  store_flags(Y + (size_t)t * (size_t)H16 + col, acc.result());
+#else
   store_stream(Y + (size_t)t * (size_t)H16 + col, acc.result());
+#endif
 }
 
 template <int DT>

@@ -36,35 +36,49 @@ __device__ __forceinline__ unsigned long long match_any(int id, bool valid, int 
   return mask;
 }
 
-// Inclusive prefix sum across the 64 lanes of a wave.
+// Inclusive prefix sum across the 64 lanes of a wave with DPP row shifts and row broadcasts (no LDS
+// traffic): shifts by 1,2,4,8 inside each row of 16 lanes, then the last lane of row 0/2 is added
+// to row 1/3 and the last lane of the lower half to the upper half.
 __device__ __forceinline__ int wave_inclusive_scan(int v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const int up = __shfl_up(v, d, kWave);
-    if (lane >= d) v += up;
-  }
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2 and 3
   return v;
 }
 
 // Exclusive prefix sum of total[0..E) into g[0..E], g[E] = grand total; executed by ONE wave
-// (all 64 lanes of it must call).  Each lane owns a run of consecutive experts.
-__device__ __forceinline__ void wave_exclusive_scan_lds(const int *total, int *g, int E) {
+// (all 64 lanes of it must call).  Each lane owns a run of consecutive experts; E <= 1024.
+// Only the bits of total[] selected by `mask` are counts.
+__device__ __forceinline__ void wave_exclusive_scan_lds(const int *total, int *g, int E, int mask = -1) {
+  constexpr int kMaxPer = 16;
   const int lane = lane_id();
   const int per = (E + kWave - 1) / kWave;
   const int b = lane * per;
+  int c[kMaxPer];
+#pragma unroll
+  for (int x = 0; x < kMaxPer; ++x) c[x] = (x < per && b + x < E) ? (total[b + x] & mask) : 0;
   int sum = 0;
-  for (int x = 0; x < per; ++x)
-    if (b + x < E) sum += total[b + x];
+#pragma unroll
+  for (int x = 0; x < kMaxPer; ++x) sum += c[x];
   const int incl = wave_inclusive_scan(sum);
   int run = incl - sum;
-  for (int x = 0; x < per; ++x)
-    if (b + x < E) {
-      g[b + x] = run;
-      run += total[b + x];
-    }
+#pragma unroll
+  for (int x = 0; x < kMaxPer; ++x) {
+    if (x < per && b + x < E) g[b + x] = run;
+    run += c[x];
+  }
   if (lane == kWave - 1) g[E] = incl;
 }
+
+// Experiment hook: a 16-byte global store with an explicit cache-policy suffix.
+#ifdef MOE_EXP_STORE_FLAGS
+__device__ __forceinline__ void store_flags(u32x4 *p, u32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off " MOE_EXP_STORE_FLAGS : : "v"(p), "v"(v) : "memory");
+}
+#endif
 
 // Streaming 16-byte accesses: the payload is touched once by these kernels.
 __device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }

@@ -53,6 +53,9 @@ __global__ __launch_bounds__(kPlanBlock) void plan_tile_hist_kernel(const int32_
   for (int e = threadIdx.x; e <= E; e += kPlanBlock) out[e] = hist[e];
 }
 
+// ROUNDS > 0: a wave's segment is ROUNDS*64 branches and its ids stay in registers between the
+// counting pass and the ranking pass (tile = ROUNDS*256); ROUNDS == 0: any tile size, ids are re-read.
+template <int ROUNDS>
 __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__restrict__ K,
                                                                 const int32_t *__restrict__ tile_hist, int tiles,
                                                                 int tile, Dims d, PlanView p) {
@@ -67,16 +70,35 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   int *misc = wcur + kPlanWaves * E;   // [2]    {invalid ids, scratch counter}
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int me = blockIdx.x;
+  const int seg = tile / kPlanWaves;
+  const long long seg_start = (long long)me * tile + (long long)wave * seg;
+  const int rounds = ROUNDS > 0 ? ROUNDS : seg / kWave;
 
-  // column sums of the tile histograms: earlier tiles (start of this tile's streams) and all tiles
+  // this wave's ids: issued first so that their latency overlaps the histogram walk
+  constexpr int R = ROUNDS > 0 ? ROUNDS : 1;
+  int ids[R];
+  if (ROUNDS > 0) {
+#pragma unroll
+    for (int rd = 0; rd < R; ++rd) {
+      const long long i = seg_start + (long long)rd * kWave + lane;
+      ids[rd] = i < d.N ? K[i] : -1;
+    }
+  }
+
+  // column sums of the tile histograms: earlier tiles (start of this tile's streams) and all tiles;
+  // 32 independent loads per batch
   for (int e = tid; e <= E; e += kPlanBlock) {
     int bef = 0, all = 0;
     const int32_t *col = tile_hist + e;
-#pragma unroll 8
-    for (int t = 0; t < tiles; ++t) {
-      const int v = col[(size_t)t * (E + 1)];
-      all += v;
-      if (t < me) bef += v;
+    for (int t0 = 0; t0 < tiles; t0 += 32) {
+      int v[32];
+#pragma unroll
+      for (int u = 0; u < 32; ++u) v[u] = (t0 + u < tiles) ? col[(size_t)(t0 + u) * (E + 1)] : 0;
+#pragma unroll
+      for (int u = 0; u < 32; ++u) {
+        all += v[u];
+        if (t0 + u < me) bef += v[u];
+      }
     }
     if (e < E) {
       total[e] = all;
@@ -88,28 +110,24 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   for (int x = tid; x < kPlanWaves * E; x += kPlanBlock) wcur[x] = 0;
   __syncthreads();
   if (wave == 0) wave_exclusive_scan_lds(total, g, E);
+  // histogram of each wave's contiguous segment (counts only: atomics are order-free here)
+  for (int rd = 0; rd < rounds; ++rd) {
+    int e;
+    if (ROUNDS > 0) {
+      e = ids[rd % R];
+    } else {
+      const long long i = seg_start + (long long)rd * kWave + lane;
+      e = i < d.N ? K[i] : -1;
+    }
+    if (e >= 0 && e < E) atomicAdd(&wcur[wave * E + e], 1);
+  }
   __syncthreads();
+  // o and the region limit per expert; exclusive prefix of the segment counts over waves, seeded with
+  // the count in earlier tiles: wcur[w][e] becomes the small offset of the first branch of expert e
+  // in wave w's segment
   for (int e = tid; e < E; e += kPlanBlock) {
     off[e] = expert_first_row(g, e, d);
     lim[e] = region_row_limit(e, d);
-  }
-  if (me == 0) write_plan_tables(total, g, d, p, misc[0], misc + 1);
-
-  // histogram of each wave's contiguous segment (counts only: atomics are order-free here)
-  const int seg = tile / kPlanWaves;
-  const long long seg_start = (long long)me * tile + (long long)wave * seg;
-  const int rounds = seg / kWave;
-  for (int rd = 0; rd < rounds; ++rd) {
-    const long long i = seg_start + (long long)rd * kWave + lane;
-    if (i < d.N) {
-      const int e = K[i];
-      if (e >= 0 && e < E) atomicAdd(&wcur[wave * E + e], 1);
-    }
-  }
-  __syncthreads();
-  // exclusive prefix over waves, seeded with the count in earlier tiles: wcur[w][e] becomes the
-  // small offset of the first branch of expert e in wave w's segment
-  for (int e = tid; e < E; e += kPlanBlock) {
     int run = before[e];
     for (int w = 0; w < kPlanWaves; ++w) {
       const int c = wcur[w * E + e];
@@ -118,6 +136,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
     }
   }
   __syncthreads();
+  if (me == 0) write_plan_tables(total, g, d, p, misc[0], misc + 1);
 
   // stable ranks inside each wave segment: 64 branches per round, rounds in index order.  Among
   // lanes with the same id the lowest lane advances the running count and hands the old value out.
@@ -126,7 +145,9 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   for (int rd = 0; rd < rounds; ++rd) {
     const long long i = seg_start + (long long)rd * kWave + lane;
     const bool in = i < d.N;
-    const int e = in ? K[i] : -1;
+    int e;
+    if (ROUNDS > 0) e = ids[rd % R];
+    else e = in ? K[i] : -1;
     const bool valid = e >= 0 && e < E;
     const unsigned long long peers = match_any(e, valid, bits);
     const int leader = valid ? __ffsll((long long)peers) - 1 : lane;
@@ -181,7 +202,10 @@ hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32
   hipError_t err = launch(plan_tile_hist_kernel, dim3(tiles), dim3(kPlanBlock), lds1, s, K, d.N, d.E, tile, tile_hist);
   if (err != hipSuccess) return err;
   const size_t lds2 = (size_t)(5 * d.E + 1 + kPlanWaves * d.E + 2) * sizeof(int);
-  return launch(plan_rank_kernel, dim3(tiles), dim3(kPlanBlock), lds2, s, K, tile_hist, tiles, tile, d, p);
+  if (tile == kPlanMinTile)
+    return launch(plan_rank_kernel<kPlanMinTile / kPlanBlock>, dim3(tiles), dim3(kPlanBlock), lds2, s, K, tile_hist,
+                  tiles, tile, d, p);
+  return launch(plan_rank_kernel<0>, dim3(tiles), dim3(kPlanBlock), lds2, s, K, tile_hist, tiles, tile, d, p);
 }
 
 }  // namespace moe_rbf

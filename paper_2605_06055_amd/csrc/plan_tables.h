@@ -24,16 +24,17 @@ __device__ __forceinline__ int region_row_limit(int e, const Dims &d) {
 // copies of total[0..E) and g[0..E].  Must be called by every thread of the workgroup.
 // Branches dropped for capacity: rows of region r are packed, so exactly max(0, c_rank[r] - stride)
 // of them fall past the region's end.
+// Only the bits of total[] selected by `mask` are counts.
 __device__ __forceinline__ void write_plan_tables(const int *total, const int *g, const Dims &d, const PlanView &p,
-                                                  int n_invalid, int *lds_counter) {
+                                                  int n_invalid, int *lds_counter, int mask = -1) {
   const int nthreads = blockDim.x;
   const bool fixed = d.stride > 0;
   for (int e = threadIdx.x; e < d.E; e += nthreads) {
-    p.expert_count[e] = total[e];
+    p.expert_count[e] = total[e] & mask;
     p.expert_offset[e] = expert_first_row(g, e, d);
   }
   if (threadIdx.x == 0) {
-    p.expert_offset[d.E] = expert_first_row(g, d.E - 1, d) + total[d.E - 1];
+    p.expert_offset[d.E] = expert_first_row(g, d.E - 1, d) + (total[d.E - 1] & mask);
     p.region_base[d.R] = fixed ? (int)(d.R * d.stride) : g[d.E];
     *lds_counter = 0;
   }

@@ -144,6 +144,7 @@ def test_full_size_prefill_configs(moe, name):
     (333, 1032, 3, 1024, 64),    # E at the limit, rows of 129 vectors (ragged chunk)
     (2049, 512, 1, 4, 1),        # k = 1, one region
     (129, 8, 16, 16, 16),        # 16-byte rows, E = R
+    (70001, 8, 8, 64, 8),        # 560008 branches: more than 512 minimum-size plan tiles, so tiles grow
 ])
 @pytest.mark.parametrize("dtype", [wl.DTYPE_BF16, wl.DTYPE_F32])
 def test_ragged_shapes(moe, T, H, k, E, R, dtype):
