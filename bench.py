@@ -154,11 +154,12 @@ def cpu_baseline(cfg, budget_s=12.0):
 
 
 def traffic_for(kernel):
-    """HBM bytes per launch measured with rocprofv3 --pmc (committed summary), or None."""
+    """HBM bytes per launch measured with rocprofv3 --pmc (committed summary of two counter runs,
+    scaled by a plain copy of known size), or None when no summary covers this kernel and workload."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
-        return json.load(open(path)).get(kernel)
-    except (OSError, ValueError):
+        return json.load(open(path))[kernel]["total_bytes"]
+    except (OSError, ValueError, KeyError):
         return None
 
 
@@ -170,6 +171,9 @@ def main():
     ap.add_argument("--workload", default="prefill", choices=sorted(DESCR))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode T=128 leg of the headline run")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain elementwise copy of known size (512 MiB read + 512 MiB written, "
+                         "torch.mul(src, 1, out=dst)) so that rocprofv3 --pmc counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the dispatch/combine path; this build has no multi-GPU "
@@ -182,6 +186,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     moe.load_library()
     torch.cuda.set_device(0)
+
+    if args.calibrate:
+        src = torch.ones(128 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg = wl.CONFIGS[args.workload]
     n_sets = 20 if cfg.payload_bytes < 512e6 else 1
