@@ -16,17 +16,6 @@ namespace moe_rbf {
 #ifndef MOE_COMBINE_BLOCK
 #define MOE_COMBINE_BLOCK 128
 #endif
-#ifndef MOE_COMBINE_SLICES
-#define MOE_COMBINE_SLICES 0
-#endif
-#ifndef MOE_COMBINE_NT
-#define MOE_COMBINE_NT 1
-#endif
-#if MOE_COMBINE_NT
-#define MOE_COMBINE_LOAD(p) load_stream(p)
-#else
-#define MOE_COMBINE_LOAD(p) (*(p))
-#endif
 
 constexpr int kGather = 8;  // rows fetched together
 
@@ -98,14 +87,8 @@ __global__ __launch_bounds__(BLOCK) void combine_rows_kernel(const u32x4 *__rest
   const int k = KFIX > 0 ? KFIX : k_arg;
   const int t = blockIdx.x / chunks;
   const int c = blockIdx.x - t * chunks;
-#if MOE_COMBINE_SLICES
-  const int slice = (H16 + chunks - 1) / chunks;
-  const int col = c * slice + threadIdx.x;
-  if ((int)threadIdx.x >= slice || col >= H16) return;
-#else
   const int col = c * BLOCK + threadIdx.x;
   if (col >= H16) return;
-#endif
   const int32_t *rows = row_map + (size_t)t * k;
   const float *w = W + (size_t)t * k;
   const u32x4 *base = Yexp + col;
@@ -124,38 +107,19 @@ __global__ __launch_bounds__(BLOCK) void combine_rows_kernel(const u32x4 *__rest
     }
 #pragma unroll
     for (int u = 0; u < G; ++u)
-      y[u] = row[u] >= 0 ? MOE_COMBINE_LOAD(base + (size_t)row[u] * (size_t)H16) : u32x4{0u, 0u, 0u, 0u};
-#if MOE_EXP_NOMATH
-    u32x4 z = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int u = 0; u < G; ++u) z ^= y[u];
-    acc.a[0] += __uint_as_float(z.x ^ z.y ^ z.z ^ z.w) * wj[0];
-#else
+      y[u] = row[u] >= 0 ? load_stream(base + (size_t)row[u] * (size_t)H16) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
     for (int u = 0; u < G; ++u)
       if (row[u] >= 0) acc.fma(wj[u], y[u]);
-#endif
   }
-#if MOE_EXP_NOSTORE
-  if (acc.a[0] == 1.2345f)
-#endif
-#ifdef MOE_EXP_STORE_FLAGS
-  store_flags(Y + (size_t)t * (size_t)H16 + col, acc.result());
-#else
   store_stream(Y + (size_t)t * (size_t)H16 + col, acc.result());
-#endif
 }
 
 template <int DT>
 static hipError_t launch_combine_dt(const Dims &d, const void *expert_out, const float *W, const PlanView &p, void *y,
                                     hipStream_t s) {
   constexpr int B = MOE_COMBINE_BLOCK;
-#if MOE_COMBINE_SLICES
-  const int per = (d.H16 + 7) / 8;                        // 8 slices, more if a slice exceeds the block
-  const int chunks = 8 * ((per + B - 1) / B);
-#else
   const int chunks = (d.H16 + B - 1) / B;
-#endif
   const dim3 grid((unsigned)d.T * (unsigned)chunks);
   auto go = [&](auto kernel) {
     return launch(kernel, grid, dim3(B), 0, s, (const u32x4 *)expert_out, W, (const int32_t *)p.row_map, (u32x4 *)y,

@@ -73,13 +73,6 @@ __device__ __forceinline__ void wave_exclusive_scan_lds(const int *total, int *g
   if (lane == kWave - 1) g[E] = incl;
 }
 
-// Experiment hook: a 16-byte global store with an explicit cache-policy suffix.
-#ifdef MOE_EXP_STORE_FLAGS
-__device__ __forceinline__ void store_flags(u32x4 *p, u32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off " MOE_EXP_STORE_FLAGS : : "v"(p), "v"(v) : "memory");
-}
-#endif
-
 // Streaming 16-byte accesses: the payload is touched once by these kernels.
 __device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void store_stream(u32x4 *p, u32x4 v) { __builtin_nontemporal_store(v, p); }

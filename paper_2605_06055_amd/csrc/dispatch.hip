@@ -3,13 +3,8 @@
 // No staging copy exists: HBM traffic is T*H bytes read and T*k*H bytes written.
 //
 // Prefill schedule (row map from moe_plan): XCD-affine column slices, see dispatch_slices_kernel.
-// Decode schedule: ONE launch.  Every workgroup rebuilds the plan values it needs from the routing
-//   ids (LDS histogram of all ids with the count of ids before its token packed into the same word,
-//   exclusive scan), so counts, offsets, small offsets and payload placement need no grid-wide
-//   synchronisation; the chunk-0 workgroup of a token records that token's s and row map and
-//   workgroup 0 records the tables that combine and the expert stage read.
-//   The kernel is latency-bound (a few microseconds), so its hot path is kept small in code size:
-//   rare paths are branched over.
+// Decode schedule: ONE launch, no grid-wide synchronisation: every workgroup derives the rows of its
+//   token from the routing ids themselves (see the decode section below).
 #include "device_utils.h"
 #include "launch.h"
 #include "plan_tables.h"
@@ -17,7 +12,7 @@
 namespace moe_rbf {
 
 #ifndef MOE_DECODE_BLOCK
-#define MOE_DECODE_BLOCK 448
+#define MOE_DECODE_BLOCK 512
 #endif
 #ifndef MOE_DECODE_VEC
 #define MOE_DECODE_VEC 1
@@ -54,26 +49,35 @@ __global__ __launch_bounds__(BLOCK) void dispatch_slices_kernel(const u32x4 *__r
 }
 
 // ---- decode -------------------------------------------------------------------------------------
+//
+// Row of branch (t,j) with expert e:  region/expert base + #{ids i : lo <= K_i < e} + #{i < t*k+j : K_i = e}
+// (lo = 0 and base = 0 for tight windows; lo = first expert of e's rank and base = rank*stride otherwise).
+// Both terms are plain counts over the <= 8192 routing ids of the batch, so a payload workgroup gets
+// them with compares on the ids it holds in registers, wave ballots (the counts land in scalar
+// registers) and one LDS exchange between its waves: no histogram, no scan, one barrier.  The two counts of a slot travel packed in
+// one word (low 16 bits: ids below e; high 16 bits: equal ids in front of the branch).
+// One extra workgroup (the last) builds the histogram and writes the tables for combine and the experts.
 
-// Rows of a token with more slots than one wave can rank with ballots (k > 64): plain loops.
-__device__ __forceinline__ void decode_rows_large_k(const int *tok, const int *packed, const int *g, int *rows,
-                                                 const Dims &d, const PlanView &p, int first, bool record) {
-  for (int j = threadIdx.x; j < d.k; j += blockDim.x) {
-    const int e = tok[j];
-    int s = -1, row = -1;
-    if (e >= 0 && e < d.E) {
-      int dup = 0;
-      for (int jp = 0; jp < j; ++jp) dup += (tok[jp] == e);
-      s = (packed[e] >> 16) + dup;
-      row = expert_first_row(g, e, d) + s;
-      if (row >= region_row_limit(e, d)) row = -1;
-    }
-    rows[j] = row;
-    if (record) {
-      if (p.send_idx) p.send_idx[first + j] = s;
-      p.row_map[first + j] = row;
-    }
+constexpr int kSlotBatch = 8;     // slots of a token ranked together
+
+__device__ __forceinline__ void decode_tables_block(const int32_t *__restrict__ K, const Dims &d, const PlanView &p,
+                                                    int *lds) {
+  const int E = d.E, tid = threadIdx.x, nthreads = blockDim.x;
+  int *total = lds;            // [E]
+  int *g = total + E;          // [E+1]
+  int *misc = g + E + 1;       // [2]
+  for (int e = tid; e < E; e += nthreads) total[e] = 0;
+  if (tid == 0) misc[0] = 0;
+  __syncthreads();
+  for (int i = tid; i < d.N; i += nthreads) {
+    const int e = K[i];
+    if (e >= 0 && e < E) atomicAdd(&total[e], 1);
+    else if (e != -1) atomicAdd(&misc[0], 1);
   }
+  __syncthreads();
+  if (tid < kWave) wave_exclusive_scan_lds(total, g, E);
+  __syncthreads();
+  write_plan_tables(total, g, d, p, misc[0], misc + 1);
 }
 
 template <int BLOCK, int V>
@@ -81,20 +85,19 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
                                                                 const int32_t *__restrict__ K,
                                                                 u32x4 *__restrict__ window, Dims d, PlanView p,
                                                                 int chunks) {
-  extern __shared__ int lds[];
-  const int E = d.E;
-  int *total = lds;              // [E]   low half: c^exp; high half: branches of expert e with a flat index
-                                 //       below this token's first slot
-  int *g = total + E;            // [E+1] exclusive scan of c^exp
-  int *rows = g + E + 1;         // [k]   destination rows of this token
-  int *tok = rows + d.k;         // [k]   routing ids of this token
-  int *misc = tok + d.k;         // [2]   {invalid ids, scratch counter}
-  const int tid = threadIdx.x;
+  extern __shared__ int lds[];                                  // tables workgroup only
+  __shared__ int part[(BLOCK / kWave) * kSlotBatch];            // per-wave packed counts of a slot batch
+  constexpr int kWaves = BLOCK / kWave;
+  if ((int)blockIdx.x == d.T * chunks) {
+    decode_tables_block(K, d, p, lds);
+    return;
+  }
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int t = blockIdx.x / chunks;
   const int c = blockIdx.x - t * chunks;
   const int first = t * d.k;
 
-  // everything that comes from memory is requested up front: payload, all routing ids, own ids
+  // everything that comes from memory is requested up front: payload, routing ids, own slots' ids
   const int col0 = c * (BLOCK * V) + tid;
   const u32x4 *src = X + (size_t)t * (size_t)d.H16;
   u32x4 v[V];
@@ -103,70 +106,77 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
     const int col = col0 + x * BLOCK;
     v[x] = col < d.H16 ? load_stream(src + col) : u32x4{0u, 0u, 0u, 0u};
   }
-  constexpr int kIds = 4;        // ids per thread and pass
+  constexpr int kIds = 4;        // ids per thread kept in registers (first kIds passes over K)
   int id[kIds];
 #pragma unroll
   for (int u = 0; u < kIds; ++u) {
     const int i = u * BLOCK + tid;
     id[u] = i < d.N ? K[i] : -1;
   }
-  for (int j = tid; j < d.k; j += BLOCK) tok[j] = K[first + j];
-  for (int e = tid; e < E; e += BLOCK) total[e] = 0;
-  if (tid == 0) misc[0] = 0;
-  __syncthreads();
 
-  // one LDS atomic per id: +1 counts the id, +0x10000 also counts it as "before this token"
-  // (T*k <= 8192, so neither half can overflow 16 bits)
-  for (int i0 = 0; i0 < d.N; i0 += BLOCK * kIds) {
+  const bool fixed = d.stride > 0;
+  for (int j0 = 0; j0 < d.k; j0 += kSlotBatch) {
+    // lane u < 8 of every wave owns slot j0+u
+    const bool own = lane < kSlotBatch && j0 + lane < d.k;
+    const int my_e = own ? K[first + j0 + lane] : -1;
+    const bool my_valid = my_e >= 0 && my_e < d.E;
+    const int my_rank = my_valid ? my_e / d.Er : 0;
+    const int my_lo = fixed ? my_rank * d.Er : 0;
+    int e[kSlotBatch], lo[kSlotBatch], below[kSlotBatch], front[kSlotBatch];
 #pragma unroll
-    for (int u = 0; u < kIds; ++u) {
-      const int i = i0 + u * BLOCK + tid;
-      const int e = i0 == 0 ? id[u] : (i < d.N ? K[i] : -1);
-      if (e >= 0 && e < E) atomicAdd(&total[e], i < first ? 0x10001 : 1);
-      else if (e != -1) atomicAdd(&misc[0], 1);
+    for (int u = 0; u < kSlotBatch; ++u) {
+      e[u] = __builtin_amdgcn_readlane(my_e, u);
+      lo[u] = __builtin_amdgcn_readlane(my_lo, u);
+      below[u] = 0;
+      front[u] = 0;
     }
-  }
-  __syncthreads();
-  if (tid < kWave) wave_exclusive_scan_lds(total, g, E, 0xffff);
-  __syncthreads();
-
-  // small offset = count in earlier tokens + earlier slots of this token with the same id
-  if (d.k <= kWave) {
-    if (tid < kWave) {   // one wave: equal ids among the token's slots are found with ballots
-      const bool in = tid < d.k;
-      const int e = in ? tok[tid] : -1;
-      const bool valid = e >= 0 && e < E;
-      const unsigned long long peers = match_any(e, valid, id_bits(E));
-      int s = -1, row = -1;
-      if (valid) {
-        s = (total[e] >> 16) + __popcll(peers & ((1ull << tid) - 1ull));
-        row = expert_first_row(g, e, d) + s;
-        if (row >= region_row_limit(e, d)) row = -1;
+    // wave-wide counts by ballot: they land in scalar registers, no lane reduction is needed
+    for (int i0 = 0, pass = 0; i0 < d.N; i0 += BLOCK, ++pass) {
+      const int i = i0 + tid;
+      int x;
+      if (pass < kIds) {
+        x = id[0];
+#pragma unroll
+        for (int q = 1; q < kIds; ++q) x = pass == q ? id[q] : x;
+      } else {
+        x = i < d.N ? K[i] : -1;
       }
-      if (in) {
-        rows[tid] = row;
-        if (c == 0) {
-          if (p.send_idx) p.send_idx[first + tid] = s;
-          p.row_map[first + tid] = row;
-        }
+      const int ahead = first + j0 - i;               // slot u is behind id i  <=>  u + ahead > 0
+#pragma unroll
+      for (int u = 0; u < kSlotBatch; ++u) {
+        // ids outside [0,E) never satisfy either test: x - lo wraps to a huge unsigned value or x > e
+        below[u] += __popcll(__ballot((unsigned)(x - lo[u]) < (unsigned)(e[u] - lo[u])));
+        front[u] += __popcll(__ballot(x == e[u] && ahead + u > 0));
       }
     }
-  } else {
-    decode_rows_large_k(tok, total, g, rows, d, p, first, c == 0);
-  }
-  if (blockIdx.x == 0) write_plan_tables(total, g, d, p, misc[0], misc + 1, 0xffff);
-  __syncthreads();
-
-  // fan the chunk out to the token's destination rows; lane j of every wave holds row j of a batch of
-  // up to 64 slots, so the loop reads LDS once and then only moves lanes into scalar registers
-  for (int j0 = 0; j0 < d.k; j0 += kWave) {
-    const int slot = j0 + (tid & (kWave - 1));
-    const int mine = slot < d.k ? rows[slot] : -1;
-    const int nb = min(kWave, d.k - j0);
-    for (int j = 0; j < nb; ++j) {
-      const int row = __builtin_amdgcn_readlane(mine, j);
-      if (row < 0) continue;
-      u32x4 *dst = window + (size_t)row * (size_t)d.H16;
+    if (j0 > 0) __syncthreads();                      // the previous batch's exchange has been read
+    {
+      int mine = 0;                                   // lane u carries this wave's packed counts of slot u
+#pragma unroll
+      for (int u = 0; u < kSlotBatch; ++u) mine = lane == u ? below[u] + (front[u] << 16) : mine;
+      if (lane < kSlotBatch) part[wave * kSlotBatch + lane] = mine;
+    }
+    __syncthreads();
+    int packed = 0;
+    if (lane < kSlotBatch)
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) packed += part[w * kSlotBatch + lane];
+    int s = -1, row = -1;
+    if (own && my_valid) {
+      s = packed >> 16;
+      row = (fixed ? (int)(my_rank * d.stride) : 0) + (packed & 0xffff) + s;
+      if (fixed && row >= (int)((my_rank + 1) * d.stride)) row = -1;
+    }
+    if (own && c == 0 && wave == 0) {
+      if (p.send_idx) p.send_idx[first + j0 + lane] = s;
+      p.row_map[first + j0 + lane] = row;
+    }
+    // fan the chunk out to this batch's destination rows
+    const int nb = min(kSlotBatch, d.k - j0);
+    for (int u = 0; u < nb; ++u) {
+      const int r = __builtin_amdgcn_readlane(row, u);
+      if (r < 0) continue;
+      u32x4 *dst = window + (size_t)r * (size_t)d.H16;
 #pragma unroll
       for (int x = 0; x < V; ++x) {
         const int col = col0 + x * BLOCK;
@@ -200,8 +210,8 @@ hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K
                                   hipStream_t s) {
   constexpr int B = MOE_DECODE_BLOCK, V = MOE_DECODE_VEC;
   const int chunks = (d.H16 + B * V - 1) / (B * V);
-  const size_t lds = (size_t)(2 * d.E + 1 + 2 * d.k + 2) * sizeof(int);
-  return launch(decode_dispatch_kernel<B, V>, dim3((unsigned)d.T * (unsigned)chunks), dim3(B), lds, s,
+  const size_t lds = (size_t)(2 * d.E + 1 + 2) * sizeof(int);
+  return launch(decode_dispatch_kernel<B, V>, dim3((unsigned)d.T * (unsigned)chunks + 1u), dim3(B), lds, s,
                 (const u32x4 *)x, K, (u32x4 *)window, d, p, chunks);
 }
 
