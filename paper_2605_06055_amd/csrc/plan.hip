@@ -5,24 +5,27 @@
 // The small offset must be the number of EARLIER branches (smaller flat index t*k+j) with the same
 // expert, so it cannot come from global atomics (arbitrary order).  It is built the way the paper
 // describes the Layout kernel -- per-block counting plus prefix accumulation over earlier blocks:
-//   K1  plan_tile_hist : one workgroup per tile of branches -> LDS histogram -> tile_hist[tile][E+1]
-//                        (slot E counts ids outside [0,E) other than -1)
-//   K2  plan_rank      : one workgroup per tile; column sums of tile_hist over earlier tiles give the
-//                        tile's starting count per expert; every workgroup also forms the totals and
-//                        their exclusive scan (cheap, E <= 1024) so no third launch is needed; inside
-//                        the tile each of the 4 waves owns a contiguous segment, segment histograms are
-//                        prefix-summed in wave order, and inside a wave the rank among lanes holding the
-//                        same id comes from ballots.  Integer LDS atomics are used for COUNTS only,
-//                        which do not depend on order.
+//   pass 1  plan_tile_hist : one workgroup per tile of branches -> LDS histogram -> tile_hist[tile][E+1]
+//                            (slot E counts ids outside [0,E) other than -1)
+//   pass 2  plan_rank      : one workgroup (16 waves) per tile.  Column sums of tile_hist over earlier
+//                            tiles give the tile's starting count per expert; every workgroup also forms
+//                            the totals and their exclusive scan (cheap, E <= 1024), so there is no third
+//                            launch.  Each wave owns a contiguous segment of the tile; segment histograms
+//                            are prefix-summed over the waves with a DPP row scan, and inside a wave the
+//                            rank among lanes holding the same id comes from ballots.  Integer LDS atomics
+//                            are used for COUNTS only, which do not depend on order.  One extra workgroup
+//                            writes the count/offset tables.
+// Both kernels are latency-bound (a few microseconds): loads are requested before LDS is cleared and
+// the serial chain is kept to three barriers.
 #include "device_utils.h"
 #include "launch.h"
 #include "plan_tables.h"
 
 namespace moe_rbf {
 
-constexpr int kPlanBlock = 256;                   // 4 waves
+constexpr int kPlanBlock = 1024;                  // 16 waves
 constexpr int kPlanWaves = kPlanBlock / kWave;
-constexpr int kPlanMinTile = 1024;                // 4 rounds of 64 per wave
+constexpr int kPlanMinTile = kPlanBlock;          // one branch per thread
 constexpr int kPlanMaxTiles = 512;
 
 int plan_tile_size(int64_t N) {
@@ -39,12 +42,14 @@ int plan_tile_count(int64_t N) {
 __global__ __launch_bounds__(kPlanBlock) void plan_tile_hist_kernel(const int32_t *__restrict__ K, int N, int E,
                                                                      int tile, int32_t *__restrict__ tile_hist) {
   extern __shared__ int hist[];  // [E+1]
-  for (int e = threadIdx.x; e <= E; e += kPlanBlock) hist[e] = 0;
-  __syncthreads();
   const long long start = (long long)blockIdx.x * tile;
   const long long end = min(start + (long long)tile, (long long)N);
-  for (long long i = start + threadIdx.x; i < end; i += kPlanBlock) {
-    const int e = K[i];
+  const long long i0 = start + threadIdx.x;
+  const int first_id = i0 < end ? K[i0] : -1;     // requested before the histogram is cleared
+  for (int e = threadIdx.x; e <= E; e += kPlanBlock) hist[e] = 0;
+  __syncthreads();
+  for (long long i = i0; i < end; i += kPlanBlock) {
+    const int e = i == i0 ? first_id : K[i];
     if (e >= 0 && e < E) atomicAdd(&hist[e], 1);
     else if (e != -1) atomicAdd(&hist[E], 1);
   }
@@ -53,115 +58,125 @@ __global__ __launch_bounds__(kPlanBlock) void plan_tile_hist_kernel(const int32_
   for (int e = threadIdx.x; e <= E; e += kPlanBlock) out[e] = hist[e];
 }
 
-// ROUNDS > 0: a wave's segment is ROUNDS*64 branches and its ids stay in registers between the
-// counting pass and the ranking pass (tile = ROUNDS*256); ROUNDS == 0: any tile size, ids are re-read.
-template <int ROUNDS>
+// Column sums of the tile histograms, all threads of the workgroup taking part: the columns (E+1 of
+// them, the last one counting invalid ids) are split over `parts` groups of threads that take every
+// parts-th tile; partial sums meet in LDS with integer atomics (counts: order-free).
+// all_sum[0..E] gets the sum over all tiles; before_sum[0..E) (if given) the sum over tiles < me.
+// Both must be zero on entry; the caller synchronises afterwards.
+__device__ __forceinline__ void sum_tile_columns(const int32_t *__restrict__ tile_hist, int tiles, int E, int me,
+                                                 int *all_sum, int *before_sum) {
+  const int cols = E + 1;
+  const int parts = max(1, kPlanBlock / cols);
+  const int tid = threadIdx.x;
+  if (tid < parts * cols || parts == 1) {
+    const int part = parts == 1 ? 0 : tid / cols;
+    for (int col = parts == 1 ? tid : tid - part * cols; col < cols; col += kPlanBlock) {
+      int all = 0, bef = 0;
+      const int32_t *src = tile_hist + col;
+      for (int t0 = part; t0 < tiles; t0 += parts * 16) {
+        int v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const int t = t0 + u * parts;
+          v[u] = t < tiles ? src[(size_t)t * cols] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          all += v[u];
+          if (t0 + u * parts < me) bef += v[u];
+        }
+      }
+      if (all) atomicAdd(&all_sum[col], all);
+      if (before_sum && bef && col < E) atomicAdd(&before_sum[col], bef);
+    }
+  }
+}
+
+// Inclusive prefix sum inside each row of 16 consecutive lanes (DPP row shifts).
+__device__ __forceinline__ int row16_inclusive_scan(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);
+  return v;
+}
+
+// Pass 2.  Workgroups 0..tiles-1 rank one tile each; workgroup `tiles` writes the count/offset tables.
+// A tile is split into 16 contiguous wave segments (64 branches each when the tile is 1024 branches).
 __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__restrict__ K,
                                                                 const int32_t *__restrict__ tile_hist, int tiles,
                                                                 int tile, Dims d, PlanView p) {
   extern __shared__ int lds[];
   const int E = d.E;
-  int *total = lds;                    // [E]    c^exp
-  int *g = total + E;                  // [E+1]  exclusive scan of total over all experts
-  int *off = g + E + 1;                // [E]    o[e]: first row of expert e
-  int *lim = off + E;                  // [E]    first row past expert e's rank region
-  int *before = lim + E;               // [E]    branches of expert e in earlier tiles
-  int *wcur = before + E;              // [waves][E] segment histograms, then running s per wave
-  int *misc = wcur + kPlanWaves * E;   // [2]    {invalid ids, scratch counter}
+  int *total = lds;                    // [E+1]  c^exp, then the number of invalid ids
+  int *g = total + E + 1;              // [E+1]  exclusive scan of c^exp over all experts
+  int *before = g + E + 1;             // [E]    branches of expert e in earlier tiles
+  int *wcur = before + E;              // [waves][E] segment histograms, then running s per wave segment
+  int *misc = wcur + kPlanWaves * E;   // [2]    scratch
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int me = blockIdx.x;
+
+  if (me == tiles) {                   // tables workgroup
+    for (int e = tid; e <= E; e += kPlanBlock) total[e] = 0;
+    __syncthreads();
+    sum_tile_columns(tile_hist, tiles, E, 0, total, nullptr);
+    __syncthreads();
+    if (wave == 0) wave_exclusive_scan_lds(total, g, E);
+    __syncthreads();
+    write_plan_tables(total, g, d, p, total[E], misc);
+    return;
+  }
+
   const int seg = tile / kPlanWaves;
   const long long seg_start = (long long)me * tile + (long long)wave * seg;
-  const int rounds = ROUNDS > 0 ? ROUNDS : seg / kWave;
+  const int rounds = seg / kWave;
+  // the first round's id is requested before anything else and stays in a register
+  const long long i_first = seg_start + lane;
+  const int id_first = i_first < d.N ? K[i_first] : -1;
 
-  // this wave's ids: issued first so that their latency overlaps the histogram walk
-  constexpr int R = ROUNDS > 0 ? ROUNDS : 1;
-  int ids[R];
-  if (ROUNDS > 0) {
-#pragma unroll
-    for (int rd = 0; rd < R; ++rd) {
-      const long long i = seg_start + (long long)rd * kWave + lane;
-      ids[rd] = i < d.N ? K[i] : -1;
-    }
-  }
-
-  // column sums of the tile histograms: earlier tiles (start of this tile's streams) and all tiles;
-  // 32 independent loads per batch
-  for (int e = tid; e <= E; e += kPlanBlock) {
-    int bef = 0, all = 0;
-    const int32_t *col = tile_hist + e;
-    for (int t0 = 0; t0 < tiles; t0 += 32) {
-      int v[32];
-#pragma unroll
-      for (int u = 0; u < 32; ++u) v[u] = (t0 + u < tiles) ? col[(size_t)(t0 + u) * (E + 1)] : 0;
-#pragma unroll
-      for (int u = 0; u < 32; ++u) {
-        all += v[u];
-        if (t0 + u < me) bef += v[u];
-      }
-    }
-    if (e < E) {
-      total[e] = all;
-      before[e] = bef;
-    } else {
-      misc[0] = all;
-    }
-  }
+  for (int e = tid; e <= E; e += kPlanBlock) total[e] = 0;
+  for (int e = tid; e < E; e += kPlanBlock) before[e] = 0;
   for (int x = tid; x < kPlanWaves * E; x += kPlanBlock) wcur[x] = 0;
   __syncthreads();
-  if (wave == 0) wave_exclusive_scan_lds(total, g, E);
-  // histogram of each wave's contiguous segment (counts only: atomics are order-free here)
+  sum_tile_columns(tile_hist, tiles, E, me, total, before);
+  // histogram of each wave's segment (counts only: atomics are order-free here)
   for (int rd = 0; rd < rounds; ++rd) {
-    int e;
-    if (ROUNDS > 0) {
-      e = ids[rd % R];
-    } else {
-      const long long i = seg_start + (long long)rd * kWave + lane;
-      e = i < d.N ? K[i] : -1;
-    }
+    const long long i = seg_start + (long long)rd * kWave + lane;
+    const int e = rd == 0 ? id_first : (i < d.N ? K[i] : -1);
     if (e >= 0 && e < E) atomicAdd(&wcur[wave * E + e], 1);
   }
   __syncthreads();
-  // o and the region limit per expert; exclusive prefix of the segment counts over waves, seeded with
-  // the count in earlier tiles: wcur[w][e] becomes the small offset of the first branch of expert e
-  // in wave w's segment
-  for (int e = tid; e < E; e += kPlanBlock) {
-    off[e] = expert_first_row(g, e, d);
-    lim[e] = region_row_limit(e, d);
-    int run = before[e];
-    for (int w = 0; w < kPlanWaves; ++w) {
-      const int c = wcur[w * E + e];
-      wcur[w * E + e] = run;
-      run += c;
-    }
+  if (wave == 0) wave_exclusive_scan_lds(total, g, E);
+  // exclusive prefix of the segment counts over the 16 waves, seeded with the count in earlier tiles:
+  // element (e, w) sits in lane w of a 16-lane row, so one DPP row scan does it
+  for (int x0 = 0; x0 < kPlanWaves * E; x0 += kPlanBlock) {
+    const int x = x0 + tid;
+    const int e = x / kPlanWaves, w = x % kPlanWaves;
+    const bool in = x < kPlanWaves * E;
+    const int c = in ? wcur[w * E + e] : 0;
+    const int incl = row16_inclusive_scan(c);
+    if (in) wcur[w * E + e] = before[e] + incl - c;
   }
   __syncthreads();
-  if (me == 0) write_plan_tables(total, g, d, p, misc[0], misc + 1);
 
-  // stable ranks inside each wave segment: 64 branches per round, rounds in index order.  Among
-  // lanes with the same id the lowest lane advances the running count and hands the old value out.
+  // stable ranks inside each wave segment: 64 branches per round, rounds in index order.  Lanes with
+  // the same id all read the segment's running count, then the lowest of them advances it.
   const int bits = id_bits(E);
   int *mine = wcur + wave * E;
   for (int rd = 0; rd < rounds; ++rd) {
     const long long i = seg_start + (long long)rd * kWave + lane;
     const bool in = i < d.N;
-    int e;
-    if (ROUNDS > 0) e = ids[rd % R];
-    else e = in ? K[i] : -1;
+    const int e = rd == 0 ? id_first : (in ? K[i] : -1);
     const bool valid = e >= 0 && e < E;
     const unsigned long long peers = match_any(e, valid, bits);
-    const int leader = valid ? __ffsll((long long)peers) - 1 : lane;
-    int base = 0;
-    if (valid && lane == leader) {
-      base = mine[e];
-      mine[e] = base + __popcll(peers);
-    }
-    base = __shfl(base, leader, kWave);
     int s = -1, row = -1;
     if (valid) {
-      s = base + __popcll(peers & ((1ull << lane) - 1ull));
-      row = off[e] + s;
-      if (row >= lim[e]) row = -1;
+      const int base = mine[e];
+      const int rank = __popcll(peers & ((1ull << lane) - 1ull));
+      if (rank == 0 && rounds > 1) mine[e] = base + __popcll(peers);   // LDS ops of a wave execute in order
+      s = base + rank;
+      row = expert_first_row(g, e, d) + s;
+      if (row >= region_row_limit(e, d)) row = -1;
     }
     if (in) {
       if (p.send_idx) p.send_idx[i] = s;
@@ -201,11 +216,13 @@ hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32
   const size_t lds1 = (size_t)(d.E + 1) * sizeof(int);
   hipError_t err = launch(plan_tile_hist_kernel, dim3(tiles), dim3(kPlanBlock), lds1, s, K, d.N, d.E, tile, tile_hist);
   if (err != hipSuccess) return err;
-  const size_t lds2 = (size_t)(5 * d.E + 1 + kPlanWaves * d.E + 2) * sizeof(int);
-  if (tile == kPlanMinTile)
-    return launch(plan_rank_kernel<kPlanMinTile / kPlanBlock>, dim3(tiles), dim3(kPlanBlock), lds2, s, K, tile_hist,
-                  tiles, tile, d, p);
-  return launch(plan_rank_kernel<0>, dim3(tiles), dim3(kPlanBlock), lds2, s, K, tile_hist, tiles, tile, d, p);
+  const size_t lds2 = (size_t)(3 * d.E + 2 + kPlanWaves * d.E + 2) * sizeof(int);
+  if (lds2 > 64 * 1024) {   // beyond the default dynamic LDS limit (E > ~800): raise it once per process
+    static const hipError_t raised = hipFuncSetAttribute((const void *)plan_rank_kernel,
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    if (raised != hipSuccess) return raised;
+  }
+  return launch(plan_rank_kernel, dim3(tiles + 1), dim3(kPlanBlock), lds2, s, K, tile_hist, tiles, tile, d, p);
 }
 
 }  // namespace moe_rbf
