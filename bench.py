@@ -171,6 +171,9 @@ def main():
     ap.add_argument("--workload", default="prefill", choices=sorted(DESCR))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode T=128 leg of the headline run")
+    ap.add_argument("--decode-sweep", action="store_true",
+                    help="also time decode layers at the paper's Table 2 points: hidden 4096 and 7168, "
+                         "batch 16..144 (HIP graph replay, cold buffers); printed to stderr and added to the JSON")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain elementwise copy of known size (512 MiB read + 512 MiB written, "
                          "torch.mul(src, 1, out=dst)) so that rocprofv3 --pmc counters can be scaled")
@@ -232,6 +235,19 @@ def main():
                          "cache": "cold: 20 disjoint buffer sets (660 MB) rotated so no step finds its lines in "
                                   "the 256 MB Infinity Cache",
                          "kernels": {k: round(v, 2) for k, v in d["kernels"].items()}}
+    if args.decode_sweep:
+        sweep = []
+        for H in (4096, 7168):
+            for T in (16, 32, 64, 80, 128, 144):
+                c = wl.CONFIGS["decode"].with_(name=f"decode_T{T}_H{H}", T=T, H=H)
+                n_sets = max(20, int(600e6 // c.payload_bytes))
+                r = measure(c, 800, 5, min(n_sets, 200), use_graph=True)
+                row = {"H": H, "T": T, "us_per_layer": round(r["us_per_layer"], 2),
+                       "dispatch_us": round(r["kernels"]["dispatch_us"], 2),
+                       "combine_us": round(r["kernels"]["combine_us"], 2), "GBps": round(r["gbs"], 1)}
+                log(f"[decode sweep] {json.dumps(row)}")
+                sweep.append(row)
+        out["decode_sweep"] = sweep
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
         out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
