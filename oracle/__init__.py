@@ -35,7 +35,7 @@ def _load():
     if _lib is None:
         build(force=False)
         _lib = ctypes.CDLL(_LIB)
-        for name in ("moe_ref_plan", "moe_ref_dispatch", "moe_ref_combine", "moe_ref_combine_f64",
+        for name in ("moe_ref_plan", "moe_ref_plan_multi", "moe_ref_dispatch", "moe_ref_combine", "moe_ref_combine_f64",
                      "moe_ref_expert_standin"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
@@ -81,6 +81,37 @@ def plan(K: np.ndarray, E: int, R: int, region_stride_rows: int = 0) -> Plan:
                               _p(out.status))
     if rc != 0:
         raise ValueError(f"moe_ref_plan rejected the shape (rc={rc})")
+    return out
+
+
+@dataclass
+class MultiPlan(Plan):
+    o_all: np.ndarray = None         # [E,R] o_{e,r}: first row of the sub-block (expert e, source rank r)
+    recv_count: np.ndarray = None    # [E]   n^exp: rows of expert e's whole block (all sources)
+    recv_offset: np.ndarray = None   # [E+1] first row of expert e's whole block; [E] = end of the last block
+
+    @property
+    def window_rows(self) -> int:
+        return int(max(self.region_base[-1], self.recv_offset[-1]))
+
+
+def plan_multi(K: np.ndarray, M: np.ndarray, me: int, E: int, R: int, region_stride_rows: int = 0) -> MultiPlan:
+    """Plan of source rank `me` when M[r,e] branches arrive from the other source ranks (row `me` of M is ignored)."""
+    K = np.ascontiguousarray(K, dtype=np.int32)
+    M = np.ascontiguousarray(M, dtype=np.int32)
+    assert M.shape == (R, E)
+    T, k = K.shape
+    out = MultiPlan(np.zeros(E, np.int32), np.zeros(R, np.int32), np.zeros(E + 1, np.int32),
+                    np.zeros(R + 1, np.int32), np.zeros((T, k), np.int32), np.zeros((T, k), np.int32),
+                    np.zeros(2, np.int32), np.zeros((E, R), np.int32), np.zeros(E, np.int32),
+                    np.zeros(E + 1, np.int32))
+    rc = _load().moe_ref_plan_multi(ctypes.c_int32(T), ctypes.c_int32(k), ctypes.c_int32(E), ctypes.c_int32(R),
+                                    ctypes.c_int64(region_stride_rows), ctypes.c_int32(me), _p(K), _p(M),
+                                    _p(out.c_exp), _p(out.c_rank), _p(out.expert_offset), _p(out.region_base),
+                                    _p(out.s), _p(out.row_map), _p(out.status), _p(out.o_all), _p(out.recv_count),
+                                    _p(out.recv_offset))
+    if rc != 0:
+        raise ValueError(f"moe_ref_plan_multi rejected the shape (rc={rc})")
     return out
 
 

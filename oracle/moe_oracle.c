@@ -148,6 +148,79 @@ int moe_ref_plan(int32_t T, int32_t k, int32_t E, int32_t R, int64_t region_stri
   return 0;
 }
 
+/* ---- Notify with several source ranks (Section 5.2 "Prefill Notify"; Section 5.1 definition of o_{e,r}) ----
+ *
+ * M[r][e] = routed branches that source rank r sends to expert e (the gathered count matrix, recvData).
+ * This rank is source rank `me`; its row of M is replaced by the counts computed from its own K.
+ * The window of destination rank d holds the blocks of its experts in expert order, and inside an
+ * expert's block the sub-blocks of the source ranks in rank order; o_{e,r} is where sub-block (e,r)
+ * starts.  Walking (d, e, r) in that order with one running row counter IS the definition.
+ * Outputs beyond moe_ref_plan's:
+ *   o_all[e*R + r] = o_{e,r} for every source (tests check that the sub-blocks tile the window);
+ *   recv_count[e]  = sum_r M[r][e]   (n^exp: rows of expert e's whole block);
+ *   recv_offset[e] = first row of expert e's whole block; [E] = end of the last block.
+ * expert_offset[e] = o_{e,me}; row_map = o_{e,me} + s.  With a fixed region stride, region d starts at
+ * d*stride and a branch whose row falls at or past (d+1)*stride is dropped and counted in status[1].
+ */
+int moe_ref_plan_multi(int32_t T, int32_t k, int32_t E, int32_t R, int64_t region_stride_rows, int32_t me,
+                       const int32_t *K, const int32_t *M /* [R*E], row `me` ignored */,
+                       int32_t *c_exp, int32_t *c_rank, int32_t *expert_offset, int32_t *region_base,
+                       int32_t *s, int32_t *row_map, int32_t *status,
+                       int32_t *o_all /* [E*R] */, int32_t *recv_count /* [E] */, int32_t *recv_offset /* [E+1] */)
+{
+  if (T < 0 || k < 1 || E < 1 || R < 1 || E % R != 0 || me < 0 || me >= R) return -2;
+  const int32_t Er = E / R;
+  status[0] = 0;
+  status[1] = 0;
+  for (int32_t e = 0; e < E; ++e) c_exp[e] = 0;
+  /* Layout: identical to the single-source case */
+  for (int64_t i = 0; i < (int64_t)T * k; ++i) {
+    const int32_t e = K[i];
+    if (e == -1) { s[i] = -1; continue; }
+    if (e < 0 || e >= E) { status[0] += 1; s[i] = -1; continue; }
+    s[i] = c_exp[e];
+    c_exp[e] += 1;
+  }
+  for (int32_t r = 0; r < R; ++r) {
+    int32_t acc = 0;
+    for (int32_t e = r * Er; e < (r + 1) * Er; ++e) acc += c_exp[e];
+    c_rank[r] = acc;
+  }
+  /* Notify: one running row counter over (destination rank, expert, source rank) */
+  int32_t run = 0;
+  for (int32_t d = 0; d < R; ++d) {
+    if (region_stride_rows > 0) run = (int32_t)((int64_t)d * region_stride_rows);
+    region_base[d] = run;
+    for (int32_t e = d * Er; e < (d + 1) * Er; ++e) {
+      recv_offset[e] = run;
+      int32_t n = 0;
+      for (int32_t r = 0; r < R; ++r) {
+        const int32_t m = r == me ? c_exp[e] : M[(int64_t)r * E + e];
+        o_all[(int64_t)e * R + r] = run;
+        run += m;
+        n += m;
+      }
+      recv_count[e] = n;
+      expert_offset[e] = o_all[(int64_t)e * R + me];
+    }
+  }
+  recv_offset[E] = run;
+  expert_offset[E] = run;
+  region_base[R] = region_stride_rows > 0 ? (int32_t)((int64_t)R * region_stride_rows) : run;
+  for (int64_t i = 0; i < (int64_t)T * k; ++i) {
+    if (s[i] < 0) { row_map[i] = -1; continue; }
+    const int32_t e = K[i];
+    const int32_t row = expert_offset[e] + s[i];
+    if (region_stride_rows > 0 && row >= (int32_t)((int64_t)(e / Er + 1) * region_stride_rows)) {
+      status[1] += 1;
+      row_map[i] = -1;
+    } else {
+      row_map[i] = row;
+    }
+  }
+  return 0;
+}
+
 /* ---- Dispatch (Algorithm 1, first loop; Section 5.2 "Prefill Dispatch") ---- */
 
 int moe_ref_dispatch(int32_t T, int32_t H, int32_t k, int32_t elem_bytes,

@@ -287,7 +287,72 @@ def check_rounding():
     assert oracle.f64_to_bf16(d).tolist() == [0x3F81, 0x3F80, 0x3F82, 0xBF81, 0x0002, 0x0003, 0x7F80, 0x7F80]
 
 
-PINS = [check_golden, check_plan_against_library, check_masked_and_invalid, check_fixed_stride, check_dispatch,
+def check_golden_multi():
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "worked_example.json")))
+    E, R = g["E"], g["R"]
+    X = bf16(g["X"])
+    K = np.asarray(g["K"], np.int32)
+    W = np.asarray(g["W"], np.float32)
+    scale = np.asarray(g["scale"], np.float32)
+    for case in ("multi_source", "multi_source_stride_8"):
+        c = g[case]
+        pl = oracle.plan_multi(K, np.asarray(c["M"], np.int32), c["me"], E, R, c.get("stride", 0))
+        for key in ("c_exp", "c_rank", "expert_offset", "region_base", "row_map", "status", "o_all", "recv_count",
+                    "recv_offset"):
+            assert getattr(pl, key).tolist() == c[key], (case, key)
+        window = oracle.dispatch(X, pl.row_map, pl.window_rows)
+        Yexp = oracle.expert_standin(window, K, pl.row_map, scale)
+        assert np.array_equal(unbf16(oracle.combine(Yexp, W, pl.row_map)), np.asarray(c["Y"], np.float32)), case
+
+
+def check_multi_against_library(seed=6):
+    rng = np.random.default_rng(seed)
+    for T, k, E, R in ((40, 3, 12, 4), (64, 8, 32, 8), (7, 2, 6, 1), (30, 4, 8, 8)):
+        Er = E // R
+        K = wl.random_routing(rng, T, k, E, p_masked=0.1)
+        M = rng.integers(0, 9, size=(R, E)).astype(np.int32)
+        single = oracle.plan(K, E, R)
+        for me in sorted({0, R // 2, R - 1}):
+            pl = oracle.plan_multi(K, M, me, E, R)
+            full = M.copy()
+            full[me] = single.c_exp                          # own row replaced by the computed counts
+            assert np.array_equal(pl.c_exp, single.c_exp) and np.array_equal(pl.s, single.s)
+            assert np.array_equal(pl.recv_count, full.sum(0))
+            assert np.array_equal(pl.recv_offset, np.concatenate([[0], np.cumsum(full.sum(0))]))
+            # sub-blocks in (expert, source) order tile the window: exclusive cumsum of the transposed matrix
+            assert np.array_equal(pl.o_all.reshape(-1), np.concatenate([[0], np.cumsum(full.T.reshape(-1))])[:-1])
+            assert np.array_equal(pl.expert_offset[:E], pl.o_all[:, me])
+            assert pl.expert_offset[E] == full.sum() == pl.region_base[R] == pl.window_rows
+            assert np.array_equal(pl.region_base[:R], pl.recv_offset[:E:Er])
+            flat = K.reshape(-1)
+            valid = flat >= 0
+            want = np.where(valid, pl.expert_offset[np.where(valid, flat, 0)] + pl.s.reshape(-1), -1)
+            assert np.array_equal(pl.row_map.reshape(-1), want)
+            # our rows lie inside our own sub-blocks, each used once
+            rows = pl.row_map.reshape(-1)[valid]
+            assert len(np.unique(rows)) == len(rows)
+            lo = pl.o_all[flat[valid], me]
+            assert np.all((rows >= lo) & (rows < lo + single.c_exp[flat[valid]]))
+        # no traffic from the other sources: identical to the single-source plan
+        z = oracle.plan_multi(K, np.zeros((R, E), np.int32), R - 1, E, R)
+        for key in ("c_exp", "c_rank", "expert_offset", "region_base", "s", "row_map", "status"):
+            assert np.array_equal(getattr(z, key), getattr(single, key)), key
+        assert np.array_equal(z.recv_count, single.c_exp) and np.array_equal(z.recv_offset, single.expert_offset)
+        # fixed stride: regions start at d*stride; our dropped branches are those at or past the region's end
+        stride = int(full.reshape(R, R, Er).sum(axis=(0, 2)).max()) - 2 if R > 1 else int(full.sum()) - 2
+        pf = oracle.plan_multi(K, M, 0, E, R, stride)
+        assert np.array_equal(pf.region_base, np.arange(R + 1) * stride)
+        full0 = M.copy()
+        full0[0] = single.c_exp
+        start = np.arange(E) // Er * stride + (np.concatenate([[0], np.cumsum(full0.sum(0))])[:-1]
+                                               - np.repeat(np.concatenate([[0], np.cumsum(full0.sum(0))])[:-1][::Er], Er))
+        assert np.array_equal(pf.recv_offset[:E], start)
+        wantf = np.where(valid, pf.expert_offset[np.where(valid, flat, 0)] + pf.s.reshape(-1), -1)
+        dropped = valid & (wantf >= (np.where(valid, flat, 0) // Er + 1) * stride)
+        assert np.array_equal(pf.row_map.reshape(-1), np.where(dropped, -1, wantf)) and pf.status[1] == dropped.sum()
+
+
+PINS = [check_golden, check_golden_multi, check_multi_against_library, check_plan_against_library, check_masked_and_invalid, check_fixed_stride, check_dispatch,
         check_combine, check_accumulation_order, check_rounding]
 
 
@@ -369,6 +434,13 @@ MUTANTS = {
     "stride_keeps_overflow": ("if (region_stride_rows > 0 && row >= region_base[e / Er + 1]) {",
                               "if (region_stride_rows > 0 && row > region_base[e / Er + 1]) {"),
 }
+MUTANTS["multi_own_row_not_replaced"] = ("const int32_t m = r == me ? c_exp[e] : M[(int64_t)r * E + e];",
+                                         "const int32_t m = M[(int64_t)r * E + e];")
+MUTANTS["multi_sources_reversed"] = ("      for (int32_t r = 0; r < R; ++r) {\n        const int32_t m = r == me",
+                                     "      for (int32_t r = R - 1; r >= 0; --r) {\n        const int32_t m = r == me")
+MUTANTS["multi_offset_is_block_start"] = ("expert_offset[e] = o_all[(int64_t)e * R + me];", "expert_offset[e] = recv_offset[e];")
+MUTANTS["multi_stride_ignored"] = ("    if (region_stride_rows > 0) run = (int32_t)((int64_t)d * region_stride_rows);\n    region_base[d] = run;",
+                                   "    region_base[d] = run;")
 # an unstable but otherwise valid placement: reverse order inside each expert block
 MUTANTS["s_not_stable"] = ("    row_map[i] = row;\n", "    row_map[i] = expert_offset[e] + (c_exp[e] - 1 - s[i]);\n")
 
