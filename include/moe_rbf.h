@@ -54,8 +54,8 @@ enum moe_schedule { MOE_SCHEDULE_AUTO = 0, MOE_SCHEDULE_PREFILL = 1, MOE_SCHEDUL
 enum moe_status {
   MOE_OK = 0,
   MOE_ERR_NULL = -1,       /* a required pointer is NULL */
-  MOE_ERR_SHAPE = -2,      /* T<0, H<1, k<1, E<1, R<1, E%R!=0, E>MOE_MAX_EXPERTS, negative stride, unknown
-                              dtype/schedule, or DECODE forced with T*k > MOE_DECODE_MAX_BRANCHES */
+  MOE_ERR_SHAPE = -2,      /* T<0, H<1, k<1, E<1, R<1, E%R!=0, E>MOE_MAX_EXPERTS, rank_id outside [0,R), negative
+                              stride, unknown dtype/schedule, or DECODE forced with T*k > MOE_DECODE_MAX_BRANCHES */
   MOE_ERR_ALIGN = -3,      /* H*elem_bytes not a multiple of 16, or a device pointer not 16-byte aligned */
   MOE_ERR_OVERFLOW = -4,   /* T*k or the window row count does not fit in int32 */
   MOE_ERR_WORKSPACE = -5,  /* plan->workspace missing or smaller than moe_workspace_bytes */
@@ -74,7 +74,8 @@ typedef struct moe_shape {
   int32_t R;                  /* rank regions; E % R == 0 */
   int32_t dtype;              /* moe_dtype of X / window / expert_out / Y */
   int32_t schedule;           /* moe_schedule */
-  int32_t reserved;           /* must be 0 */
+  int32_t rank_id;            /* which source rank this device is, 0..R-1; only used when plan->source_count is
+                                 given (otherwise leave 0) */
   int64_t region_stride_rows; /* 0: tight windows, region r holds exactly c^rank[r] rows and the window has T*k rows.
                                  >0: symmetric windows, region r starts at row r*stride; branches that do not fit
                                  in their region are not placed (row_map = -1) and are counted in status[1]. */
@@ -97,6 +98,17 @@ typedef struct moe_plan_t {
                                     region capacity}.  Id -1 marks an unused slot and is not an error. */
   void *workspace;        /* device scratch for moe_plan, >= moe_workspace_bytes(shape); unused by DECODE dispatch */
   size_t workspace_bytes;
+  /* Several source ranks (paper, Section 5.2 "Prefill Notify": gathered count matrix M, recvData).  Optional. */
+  const int32_t *source_count; /* [R*E] in: M[r*E+e] = branches source rank r sends to expert e.  Row shape->rank_id is
+                                    ignored (this rank's counts are computed from its own ids).  NULL = this rank is the
+                                    only source.  An expert's block then holds one sub-block per source rank, in rank
+                                    order, and expert_offset[e] = o_{e,rank_id} = start of THIS rank's sub-block;
+                                    expert_offset[E] = one past the last block.  The caller, who holds M, sizes tight
+                                    windows to the sum of all counts (moe_window_rows cannot know it); rows must stay
+                                    below 2^31. */
+  int32_t *recv_count;    /* [E]    out, may be NULL: rows of expert e's whole block over all sources (n^exp,
+                                    recvTokenNumPerExpert); the rows a rank region receives (n^recv) are its segment sum */
+  int32_t *recv_offset;   /* [E+1]  out, may be NULL: first row of expert e's whole block; [E] = one past the last block */
 } moe_plan_t;
 
 /* Bytes of plan->workspace that moe_plan needs for this shape (multiple of 256, never 0). */

@@ -23,7 +23,7 @@ class MoeShape(ctypes.Structure):
     """Mirror of ``moe_shape``."""
     _fields_ = [("T", ctypes.c_int32), ("H", ctypes.c_int32), ("k", ctypes.c_int32), ("E", ctypes.c_int32),
                 ("R", ctypes.c_int32), ("dtype", ctypes.c_int32), ("schedule", ctypes.c_int32),
-                ("reserved", ctypes.c_int32), ("region_stride_rows", ctypes.c_int64)]
+                ("rank_id", ctypes.c_int32), ("region_stride_rows", ctypes.c_int64)]
 
 
 class _PlanStruct(ctypes.Structure):
@@ -31,7 +31,8 @@ class _PlanStruct(ctypes.Structure):
     _fields_ = [("expert_count", ctypes.c_void_p), ("rank_count", ctypes.c_void_p),
                 ("expert_offset", ctypes.c_void_p), ("region_base", ctypes.c_void_p),
                 ("send_idx", ctypes.c_void_p), ("row_map", ctypes.c_void_p), ("status", ctypes.c_void_p),
-                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("source_count", ctypes.c_void_p), ("recv_count", ctypes.c_void_p), ("recv_offset", ctypes.c_void_p)]
 
 
 def library_path() -> str:
@@ -127,7 +128,7 @@ def moe_resolve_schedule(shape: MoeShape) -> int:
 class MoePlan:
     """Device buffers of ``moe_plan_t`` held as torch tensors (memory plumbing only)."""
 
-    def __init__(self, shape: MoeShape, device="cuda", with_send_idx: bool = True):
+    def __init__(self, shape: MoeShape, device="cuda", with_send_idx: bool = True, source_count=None):
         import torch
         N = shape.T * shape.k
         i32 = dict(dtype=torch.int32, device=device)
@@ -139,11 +140,15 @@ class MoePlan:
         self.row_map = torch.empty(max(N, 1), **i32)
         self.status = torch.empty(4, **i32)
         self.workspace = torch.empty(moe_workspace_bytes(shape), dtype=torch.uint8, device=device)
+        self.source_count = source_count          # [R,E] int32 counts of the other source ranks, or None
+        self.recv_count = torch.empty(shape.E, **i32)
+        self.recv_offset = torch.empty(shape.E + 1, **i32)
 
     def struct(self) -> _PlanStruct:
         return _PlanStruct(_ptr(self.expert_count), _ptr(self.rank_count), _ptr(self.expert_offset),
                            _ptr(self.region_base), _ptr(self.send_idx), _ptr(self.row_map), _ptr(self.status),
-                           _ptr(self.workspace), self.workspace.numel())
+                           _ptr(self.workspace), self.workspace.numel(), _ptr(self.source_count),
+                           _ptr(self.recv_count), _ptr(self.recv_offset))
 
 
 def _plan_struct(plan) -> _PlanStruct:

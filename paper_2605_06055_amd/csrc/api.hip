@@ -22,7 +22,7 @@ int check_shape(const moe_shape *sh, Dims *d) {
   if (sh->schedule != MOE_SCHEDULE_AUTO && sh->schedule != MOE_SCHEDULE_PREFILL &&
       sh->schedule != MOE_SCHEDULE_DECODE)
     return MOE_ERR_SHAPE;
-  if (sh->reserved != 0 || sh->region_stride_rows < 0) return MOE_ERR_SHAPE;
+  if (sh->rank_id < 0 || sh->rank_id >= sh->R || sh->region_stride_rows < 0) return MOE_ERR_SHAPE;
   const int64_t N = (int64_t)sh->T * sh->k;
   if (sh->schedule == MOE_SCHEDULE_DECODE && N > MOE_DECODE_MAX_BRANCHES) return MOE_ERR_SHAPE;
   const int64_t row_bytes = (int64_t)sh->H * elem_bytes(sh->dtype);
@@ -40,6 +40,7 @@ int check_shape(const moe_shape *sh, Dims *d) {
     d->E = sh->E;
     d->R = sh->R;
     d->Er = sh->E / sh->R;
+    d->me = sh->rank_id;
     d->N = (int32_t)N;
     d->H16 = (int32_t)(row_bytes / 16);
     d->dtype = sh->dtype;
@@ -76,6 +77,11 @@ int check_plan(const moe_plan_t *pl, bool need_tables, PlanView *v) {
   v->send_idx = pl->send_idx;
   v->row_map = pl->row_map;
   v->status = pl->status;
+  v->source_count = need_tables ? pl->source_count : nullptr;
+  v->recv_count = need_tables ? pl->recv_count : nullptr;
+  v->recv_offset = need_tables ? pl->recv_offset : nullptr;
+  if (need_tables && (!aligned16(pl->source_count) || !aligned16(pl->recv_count) || !aligned16(pl->recv_offset)))
+    return MOE_ERR_ALIGN;
   return MOE_OK;
 }
 

@@ -51,15 +51,17 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
 
 // Exclusive prefix sum of total[0..E) into g[0..E], g[E] = grand total; executed by ONE wave
 // (all 64 lanes of it must call).  Each lane owns a run of consecutive experts; E <= 1024.
-// Only the bits of total[] selected by `mask` are counts.
-__device__ __forceinline__ void wave_exclusive_scan_lds(const int *total, int *g, int E, int mask = -1) {
+// Only the bits of total[] selected by `mask` are counts; `addend` (optional) is added element-wise.
+__device__ __forceinline__ void wave_exclusive_scan_lds(const int *total, int *g, int E, int mask = -1,
+                                                        const int *addend = nullptr) {
   constexpr int kMaxPer = 16;
   const int lane = lane_id();
   const int per = (E + kWave - 1) / kWave;
   const int b = lane * per;
   int c[kMaxPer];
 #pragma unroll
-  for (int x = 0; x < kMaxPer; ++x) c[x] = (x < per && b + x < E) ? (total[b + x] & mask) : 0;
+  for (int x = 0; x < kMaxPer; ++x)
+    c[x] = (x < per && b + x < E) ? (total[b + x] & mask) + (addend ? addend[b + x] : 0) : 0;
   int sum = 0;
 #pragma unroll
   for (int x = 0; x < kMaxPer; ++x) sum += c[x];

@@ -65,8 +65,15 @@ __device__ __forceinline__ void decode_tables_block(const int32_t *__restrict__ 
   const int E = d.E, tid = threadIdx.x, nthreads = blockDim.x;
   int *total = lds;            // [E]
   int *g = total + E;          // [E+1]
-  int *misc = g + E + 1;       // [2]
-  for (int e = tid; e < E; e += nthreads) total[e] = 0;
+  int *others = g + E + 1;     // [E]  several source ranks only
+  int *pre = others + E;       // [E]
+  int *misc = pre + E;         // [2]
+  const bool multi = p.source_count != nullptr;
+  for (int e = tid; e < E; e += nthreads) {
+    total[e] = 0;
+    others[e] = 0;
+    pre[e] = 0;
+  }
   if (tid == 0) misc[0] = 0;
   __syncthreads();
   for (int i = tid; i < d.N; i += nthreads) {
@@ -74,10 +81,11 @@ __device__ __forceinline__ void decode_tables_block(const int32_t *__restrict__ 
     if (e >= 0 && e < E) atomicAdd(&total[e], 1);
     else if (e != -1) atomicAdd(&misc[0], 1);
   }
+  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
   __syncthreads();
-  if (tid < kWave) wave_exclusive_scan_lds(total, g, E);
+  if (tid < kWave) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
   __syncthreads();
-  write_plan_tables(total, g, d, p, misc[0], misc + 1);
+  write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, misc[0], misc + 1);
 }
 
 template <int BLOCK, int V>
@@ -85,7 +93,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
                                                                 const int32_t *__restrict__ K,
                                                                 u32x4 *__restrict__ window, Dims d, PlanView p,
                                                                 int chunks) {
-  extern __shared__ int lds[];                                  // tables workgroup only
+  extern __shared__ int lds[];                                  // tables workgroup; several-sources prefix tables
   __shared__ int part[(BLOCK / kWave) * kSlotBatch];            // per-wave packed counts of a slot batch
   constexpr int kWaves = BLOCK / kWave;
   if ((int)blockIdx.x == d.T * chunks) {
@@ -112,6 +120,21 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
   for (int u = 0; u < kIds; ++u) {
     const int i = u * BLOCK + tid;
     id[u] = i < d.N ? K[i] : -1;
+  }
+
+  // several source ranks: rows of the other sources in front of a slot's sub-block =
+  // (their rows in the experts below e, inside the region for fixed stride) + (rows of lower ranks for e)
+  const bool multi = p.source_count != nullptr;
+  int *oth_scan = lds;             // [E+1] exclusive scan over e of the other sources' counts
+  int *others = oth_scan + d.E + 1;   // [E]
+  int *pre = others + d.E;         // [E]
+  if (multi) {
+    for (int e = tid; e < 2 * d.E; e += BLOCK) others[e] = 0;
+    __syncthreads();
+    sum_columns<true>(p.source_count, d.R, d.E, d.me, others, pre, d.E);
+    __syncthreads();
+    if (tid < kWave) wave_exclusive_scan_lds(others, oth_scan, d.E);
+    __syncthreads();
   }
 
   const bool fixed = d.stride > 0;
@@ -165,6 +188,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
     if (own && my_valid) {
       s = packed >> 16;
       row = (fixed ? (int)(my_rank * d.stride) : 0) + (packed & 0xffff) + s;
+      if (multi) row += oth_scan[my_e] - oth_scan[my_lo] + pre[my_e];
       if (fixed && row >= (int)((my_rank + 1) * d.stride)) row = -1;
     }
     if (own && c == 0 && wave == 0) {
@@ -210,7 +234,7 @@ hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K
                                   hipStream_t s) {
   constexpr int B = MOE_DECODE_BLOCK, V = MOE_DECODE_VEC;
   const int chunks = (d.H16 + B * V - 1) / (B * V);
-  const size_t lds = (size_t)(2 * d.E + 1 + 2) * sizeof(int);
+  const size_t lds = (size_t)(4 * d.E + 1 + 2) * sizeof(int);
   return launch(decode_dispatch_kernel<B, V>, dim3((unsigned)d.T * (unsigned)chunks + 1u), dim3(B), lds, s,
                 (const u32x4 *)x, K, (u32x4 *)window, d, p, chunks);
 }

@@ -17,10 +17,14 @@ struct PlanView {
   int32_t *send_idx;       // [N] or nullptr
   int32_t *row_map;        // [N]
   int32_t *status;         // [2]
+  const int32_t *source_count;  // [R*E] or nullptr
+  int32_t *recv_count;     // [E] or nullptr
+  int32_t *recv_offset;    // [E+1] or nullptr
 };
 
 struct Dims {
   int32_t T, H, k, E, R, Er;
+  int32_t me;       // this device's source rank
   int32_t N;        // T*k
   int32_t H16;      // 16-byte vectors per row
   int32_t dtype;

@@ -58,40 +58,6 @@ __global__ __launch_bounds__(kPlanBlock) void plan_tile_hist_kernel(const int32_
   for (int e = threadIdx.x; e <= E; e += kPlanBlock) out[e] = hist[e];
 }
 
-// Column sums of the tile histograms, all threads of the workgroup taking part: the columns (E+1 of
-// them, the last one counting invalid ids) are split over `parts` groups of threads that take every
-// parts-th tile; partial sums meet in LDS with integer atomics (counts: order-free).
-// all_sum[0..E] gets the sum over all tiles; before_sum[0..E) (if given) the sum over tiles < me.
-// Both must be zero on entry; the caller synchronises afterwards.
-__device__ __forceinline__ void sum_tile_columns(const int32_t *__restrict__ tile_hist, int tiles, int E, int me,
-                                                 int *all_sum, int *before_sum) {
-  const int cols = E + 1;
-  const int parts = max(1, kPlanBlock / cols);
-  const int tid = threadIdx.x;
-  if (tid < parts * cols || parts == 1) {
-    const int part = parts == 1 ? 0 : tid / cols;
-    for (int col = parts == 1 ? tid : tid - part * cols; col < cols; col += kPlanBlock) {
-      int all = 0, bef = 0;
-      const int32_t *src = tile_hist + col;
-      for (int t0 = part; t0 < tiles; t0 += parts * 16) {
-        int v[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          const int t = t0 + u * parts;
-          v[u] = t < tiles ? src[(size_t)t * cols] : 0;
-        }
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-          all += v[u];
-          if (t0 + u * parts < me) bef += v[u];
-        }
-      }
-      if (all) atomicAdd(&all_sum[col], all);
-      if (before_sum && bef && col < E) atomicAdd(&before_sum[col], bef);
-    }
-  }
-}
-
 // Inclusive prefix sum inside each row of 16 consecutive lanes (DPP row shifts).
 __device__ __forceinline__ int row16_inclusive_scan(int v) {
   v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);
@@ -109,21 +75,26 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   extern __shared__ int lds[];
   const int E = d.E;
   int *total = lds;                    // [E+1]  c^exp, then the number of invalid ids
-  int *g = total + E + 1;              // [E+1]  exclusive scan of c^exp over all experts
+  int *g = total + E + 1;              // [E+1]  exclusive scan of the block sizes over all experts
   int *before = g + E + 1;             // [E]    branches of expert e in earlier tiles
-  int *wcur = before + E;              // [waves][E] segment histograms, then running s per wave segment
+  int *others = before + E;            // [E]    branches of the other source ranks (several sources only)
+  int *pre = others + E;               // [E]    branches of the source ranks below this one
+  int *wcur = pre + E;                 // [waves][E] segment histograms, then running s per wave segment
   int *misc = wcur + kPlanWaves * E;   // [2]    scratch
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int me = blockIdx.x;
+  const bool multi = p.source_count != nullptr;
 
   if (me == tiles) {                   // tables workgroup
     for (int e = tid; e <= E; e += kPlanBlock) total[e] = 0;
+    for (int e = tid; e < 2 * E; e += kPlanBlock) others[e] = 0;     // others and pre
     __syncthreads();
-    sum_tile_columns(tile_hist, tiles, E, 0, total, nullptr);
+    sum_columns<false>(tile_hist, tiles, E + 1, 0, total, nullptr, 0);
+    if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
     __syncthreads();
-    if (wave == 0) wave_exclusive_scan_lds(total, g, E);
+    if (wave == 0) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
     __syncthreads();
-    write_plan_tables(total, g, d, p, total[E], misc);
+    write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, total[E], misc);
     return;
   }
 
@@ -135,10 +106,11 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   const int id_first = i_first < d.N ? K[i_first] : -1;
 
   for (int e = tid; e <= E; e += kPlanBlock) total[e] = 0;
-  for (int e = tid; e < E; e += kPlanBlock) before[e] = 0;
+  for (int e = tid; e < 3 * E; e += kPlanBlock) before[e] = 0;       // before, others and pre
   for (int x = tid; x < kPlanWaves * E; x += kPlanBlock) wcur[x] = 0;
   __syncthreads();
-  sum_tile_columns(tile_hist, tiles, E, me, total, before);
+  sum_columns<false>(tile_hist, tiles, E + 1, me, total, before, E);
+  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
   // histogram of each wave's segment (counts only: atomics are order-free here)
   for (int rd = 0; rd < rounds; ++rd) {
     const long long i = seg_start + (long long)rd * kWave + lane;
@@ -146,7 +118,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
     if (e >= 0 && e < E) atomicAdd(&wcur[wave * E + e], 1);
   }
   __syncthreads();
-  if (wave == 0) wave_exclusive_scan_lds(total, g, E);
+  if (wave == 0) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
   // exclusive prefix of the segment counts over the 16 waves, seeded with the count in earlier tiles:
   // element (e, w) sits in lane w of a 16-lane row, so one DPP row scan does it
   for (int x0 = 0; x0 < kPlanWaves * E; x0 += kPlanBlock) {
@@ -175,7 +147,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
       const int rank = __popcll(peers & ((1ull << lane) - 1ull));
       if (rank == 0 && rounds > 1) mine[e] = base + __popcll(peers);   // LDS ops of a wave execute in order
       s = base + rank;
-      row = expert_first_row(g, e, d) + s;
+      row = expert_first_row(g, e, d) + pre[e] + s;                    // o_{e,me} + s
       if (row >= region_row_limit(e, d)) row = -1;
     }
     if (in) {
@@ -188,26 +160,32 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   }
 }
 
-__global__ void plan_empty_kernel(Dims d, PlanView p) {
-  const bool fixed = d.stride > 0;
-  for (int e = threadIdx.x; e < d.E; e += blockDim.x) {
-    p.expert_count[e] = 0;
-    p.expert_offset[e] = fixed ? (int)((e / d.Er) * d.stride) : 0;
+// No tokens: the tables still describe the (possibly non-empty) blocks of the other source ranks.
+__global__ __launch_bounds__(kPlanBlock) void plan_empty_kernel(Dims d, PlanView p) {
+  extern __shared__ int lds[];
+  const int E = d.E;
+  int *total = lds;                    // [E]   zeros
+  int *g = total + E;                  // [E+1]
+  int *others = g + E + 1;             // [E]
+  int *pre = others + E;               // [E]
+  int *misc = pre + E;                 // [2]
+  const bool multi = p.source_count != nullptr;
+  for (int e = threadIdx.x; e < E; e += kPlanBlock) {
+    total[e] = 0;
+    others[e] = 0;
+    pre[e] = 0;
   }
-  for (int r = threadIdx.x; r < d.R; r += blockDim.x) {
-    p.rank_count[r] = 0;
-    p.region_base[r] = fixed ? (int)(r * d.stride) : 0;
-  }
-  if (threadIdx.x == 0) {
-    p.expert_offset[d.E] = fixed ? (int)(((d.E - 1) / d.Er) * d.stride) : 0;
-    p.region_base[d.R] = fixed ? (int)(d.R * d.stride) : 0;
-    p.status[0] = 0;
-    p.status[1] = 0;
-  }
+  __syncthreads();
+  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
+  __syncthreads();
+  if (threadIdx.x < kWave) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
+  __syncthreads();
+  write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, 0, misc);
 }
 
 hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s) {
-  return launch(plan_empty_kernel, dim3(1), dim3(256), 0, s, d, p);
+  const size_t lds = (size_t)(4 * d.E + 1 + 2) * sizeof(int);
+  return launch(plan_empty_kernel, dim3(1), dim3(kPlanBlock), lds, s, d, p);
 }
 
 hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, hipStream_t s) {
@@ -216,10 +194,10 @@ hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32
   const size_t lds1 = (size_t)(d.E + 1) * sizeof(int);
   hipError_t err = launch(plan_tile_hist_kernel, dim3(tiles), dim3(kPlanBlock), lds1, s, K, d.N, d.E, tile, tile_hist);
   if (err != hipSuccess) return err;
-  const size_t lds2 = (size_t)(3 * d.E + 2 + kPlanWaves * d.E + 2) * sizeof(int);
+  const size_t lds2 = (size_t)(5 * d.E + 2 + kPlanWaves * d.E + 2) * sizeof(int);
   if (lds2 > 64 * 1024) {   // beyond the default dynamic LDS limit (E > ~800): raise it once per process
     static const hipError_t raised = hipFuncSetAttribute((const void *)plan_rank_kernel,
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (raised != hipSuccess) return raised;
   }
   return launch(plan_rank_kernel, dim3(tiles + 1), dim3(kPlanBlock), lds2, s, K, tile_hist, tiles, tile, d, p);

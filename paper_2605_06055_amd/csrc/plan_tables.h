@@ -1,13 +1,23 @@
-// Shared device code of the two schedules: turning the per-expert totals and their exclusive scan
-// into the plan's count / offset tables (paper, Section 5.2 "Prefill Notify", single source rank).
+// Shared device code of the two schedules: turning per-expert counts into the plan's count / offset
+// tables (paper, Section 5.2 "Prefill Notify"; Section 5.1, definition of the large offset o_{e,r}).
+//
+// Layout of the window: destination rank d owns a region; inside it the blocks of its experts follow
+// each other; inside an expert's block the sub-blocks of the source ranks follow each other in rank
+// order.  With
+//   own[e]    = branches this rank sends to expert e                     (c^exp)
+//   others[e] = branches all OTHER source ranks send to e                (column sum of M without row me)
+//   pre[e]    = branches the source ranks BELOW this one send to e       (column sum of M over rows < me)
+//   g         = exclusive scan over e of own + others
+// the block of expert e starts at  B[e] = region_start(d) + g[e] - g[d*E_r]  and this rank's sub-block at
+// o_{e,me} = B[e] + pre[e].  With one source rank others = pre = 0.
 #pragma once
 #include "device_utils.h"
 #include "launch.h"
 
 namespace moe_rbf {
 
-// First window row of expert e's block.  g = exclusive scan of the counts over ALL experts.
-// Tight windows: region r starts where the previous one ends, so o[e] = g[e].
+// First window row of expert e's whole block.  g = exclusive scan of the block sizes over ALL experts.
+// Tight windows: region r starts where the previous one ends, so B[e] = g[e].
 // Fixed stride : region r starts at r*stride and expert blocks are packed from there.
 __device__ __forceinline__ int expert_first_row(const int *g, int e, const Dims &d) {
   if (d.stride <= 0) return g[e];
@@ -20,31 +30,74 @@ __device__ __forceinline__ int region_row_limit(int e, const Dims &d) {
   return d.stride > 0 ? (int)((e / d.Er + 1) * d.stride) : 0x7fffffff;
 }
 
-// One workgroup writes expert_count, rank_count, expert_offset, region_base and status from LDS
-// copies of total[0..E) and g[0..E].  Must be called by every thread of the workgroup.
-// Branches dropped for capacity: rows of region r are packed, so exactly max(0, c_rank[r] - stride)
-// of them fall past the region's end.
-// Only the bits of total[] selected by `mask` are counts.
-__device__ __forceinline__ void write_plan_tables(const int *total, const int *g, const Dims &d, const PlanView &p,
-                                                  int n_invalid, int *lds_counter, int mask = -1) {
+// Sums columns of a row-major int matrix src[rows][cols] with all threads of the workgroup: the columns
+// are split over `parts` groups of threads that take every parts-th row; partial sums meet in LDS with
+// integer atomics (counts: order-free).  all_sum[col] += sum over rows (without row `me` if SKIP_ME);
+// before_sum[col] += sum over rows < me (if before_sum is given; only columns < before_cols).
+// The targets must hold their starting values before the call; the caller synchronises afterwards.
+template <bool SKIP_ME>
+__device__ __forceinline__ void sum_columns(const int32_t *__restrict__ src, int rows, int cols, int me,
+                                            int *all_sum, int *before_sum, int before_cols) {
+  const int nthreads = blockDim.x;
+  const int parts = max(1, nthreads / cols);
+  const int tid = threadIdx.x;
+  if (parts > 1 && tid >= parts * cols) return;
+  const int part = parts == 1 ? 0 : tid / cols;
+  for (int col = parts == 1 ? tid : tid - part * cols; col < cols; col += nthreads) {
+    int all = 0, bef = 0;
+    const int32_t *p = src + col;
+    for (int r0 = part; r0 < rows; r0 += parts * 16) {
+      int v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int r = r0 + u * parts;
+        v[u] = (r < rows && !(SKIP_ME && r == me)) ? p[(size_t)r * cols] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        all += v[u];
+        if (r0 + u * parts < me) bef += v[u];
+      }
+    }
+    if (all) atomicAdd(&all_sum[col], all);
+    if (before_sum && bef && col < before_cols) atomicAdd(&before_sum[col], bef);
+  }
+}
+
+// One workgroup writes expert_count, rank_count, expert_offset, region_base, recv_count, recv_offset and
+// status from LDS copies of own[0..E) (count bits selected by `mask`), others/pre (nullptr with a single
+// source rank) and g[0..E].  Must be called by every thread of the workgroup.
+// Branches dropped for capacity: this rank's sub-block of expert e covers rows [o, o + own); the part at
+// or past the region's end is dropped.
+__device__ __forceinline__ void write_plan_tables(const int *own, const int *others, const int *pre, const int *g,
+                                                  const Dims &d, const PlanView &p, int n_invalid, int *lds_counter,
+                                                  int mask = -1) {
   const int nthreads = blockDim.x;
   const bool fixed = d.stride > 0;
-  for (int e = threadIdx.x; e < d.E; e += nthreads) {
-    p.expert_count[e] = total[e] & mask;
-    p.expert_offset[e] = expert_first_row(g, e, d);
-  }
-  if (threadIdx.x == 0) {
-    p.expert_offset[d.E] = expert_first_row(g, d.E - 1, d) + (total[d.E - 1] & mask);
-    p.region_base[d.R] = fixed ? (int)(d.R * d.stride) : g[d.E];
-    *lds_counter = 0;
-  }
+  if (threadIdx.x == 0) *lds_counter = 0;
   __syncthreads();
   int dropped = 0;
+  for (int e = threadIdx.x; e < d.E; e += nthreads) {
+    const int c = own[e] & mask;
+    const int block = expert_first_row(g, e, d);
+    const int o = block + (pre ? pre[e] : 0);
+    const int all = c + (others ? others[e] : 0);
+    p.expert_count[e] = c;
+    p.expert_offset[e] = o;
+    if (p.recv_count) p.recv_count[e] = all;
+    if (p.recv_offset) p.recv_offset[e] = block;
+    if (fixed) dropped += min(c, max(0, o + c - region_row_limit(e, d)));
+    if (e == d.E - 1) {
+      p.expert_offset[d.E] = block + all;
+      if (p.recv_offset) p.recv_offset[d.E] = block + all;
+      p.region_base[d.R] = fixed ? (int)(d.R * d.stride) : g[d.E];
+    }
+  }
   for (int r = threadIdx.x; r < d.R; r += nthreads) {
-    const int c = g[(r + 1) * d.Er] - g[r * d.Er];
+    int c = 0;
+    for (int e = r * d.Er; e < (r + 1) * d.Er; ++e) c += own[e] & mask;
     p.rank_count[r] = c;
     p.region_base[r] = fixed ? (int)(r * d.stride) : g[r * d.Er];
-    if (fixed && c > d.stride) dropped += c - (int)d.stride;
   }
   if (dropped) atomicAdd(lds_counter, dropped);
   __syncthreads();

@@ -29,14 +29,16 @@ class MoeLayer:
     """Buffers for shape (T,H,k,E,R): plan state, window, expert_out, Y."""
 
     def __init__(self, T, H, k, E, R, dtype=B.MOE_DTYPE_BF16, schedule=B.MOE_SCHEDULE_AUTO,
-                 region_stride_rows=0, device="cuda", separate_expert_out=True):
+                 region_stride_rows=0, device="cuda", separate_expert_out=True, source_count=None, rank_id=0,
+                 window_rows=None):
         import torch
-        self.shape = B.MoeShape(T=T, H=H, k=k, E=E, R=R, dtype=dtype, schedule=schedule, reserved=0,
+        self.shape = B.MoeShape(T=T, H=H, k=k, E=E, R=R, dtype=dtype, schedule=schedule, rank_id=rank_id,
                                 region_stride_rows=region_stride_rows)
         self.torch_dtype = torch.bfloat16 if dtype == B.MOE_DTYPE_BF16 else torch.float32
-        self.rows = B.moe_window_rows(self.shape)
+        # with several source ranks the caller, who holds the count matrix, sizes tight windows
+        self.rows = B.moe_window_rows(self.shape) if window_rows is None else window_rows
         self.schedule = B.moe_resolve_schedule(self.shape)
-        self.plan = B.MoePlan(self.shape, device=device)
+        self.plan = B.MoePlan(self.shape, device=device, source_count=source_count)
         self._plan_struct = self.plan.struct()
         self.window = torch.empty((max(self.rows, 1), H), dtype=self.torch_dtype, device=device)
         self.expert_out = (torch.empty_like(self.window) if separate_expert_out else self.window)

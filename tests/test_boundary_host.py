@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 def shape(**kw):
     base = dict(T=64, H=256, k=4, E=16, R=4, dtype=moe.MOE_DTYPE_BF16, schedule=moe.MOE_SCHEDULE_AUTO,
-                reserved=0, region_stride_rows=0)
+                rank_id=0, region_stride_rows=0)
     base.update(kw)
     return moe.MoeShape(**base)
 
@@ -55,7 +55,7 @@ def test_sizes_and_schedule():
 
 
 @pytest.mark.parametrize("kw", [dict(T=-1), dict(H=0), dict(k=0), dict(E=0), dict(R=0), dict(E=10, R=4),
-                                dict(E=2048, R=4), dict(dtype=2), dict(schedule=3), dict(reserved=1),
+                                dict(E=2048, R=4), dict(dtype=2), dict(schedule=3), dict(rank_id=4), dict(rank_id=-1),
                                 dict(region_stride_rows=-1),
                                 dict(T=2000, k=8, schedule=moe.MOE_SCHEDULE_DECODE)])
 def test_bad_shape(kw):
@@ -83,7 +83,8 @@ def test_overflow():
 def fake_plan(**kw):
     """Plan struct with fake (never dereferenced) 16-byte aligned device addresses."""
     vals = dict(expert_count=0x1000, rank_count=0x2000, expert_offset=0x3000, region_base=0x4000,
-                send_idx=0x5000, row_map=0x6000, status=0x7000, workspace=0x8000, workspace_bytes=1 << 20)
+                send_idx=0x5000, row_map=0x6000, status=0x7000, workspace=0x8000, workspace_bytes=1 << 20,
+                source_count=None, recv_count=None, recv_offset=None)
     vals.update(kw)
     return _PlanStruct(**vals)
 
@@ -117,6 +118,8 @@ def test_pointer_alignment():
     assert code(moe.moe_plan, s, 0x100, fake_plan(row_map=0x6004), 0) == -3
     assert code(moe.moe_plan, s, 0x100, fake_plan(send_idx=0x5008), 0) == -3
     assert code(moe.moe_plan, s, 0x100, fake_plan(workspace=0x8001), 0) == -3
+    assert code(moe.moe_plan, s, 0x100, fake_plan(source_count=0x9004), 0) == -3
+    assert code(moe.moe_plan, s, 0x100, fake_plan(recv_offset=0x9008), 0) == -3
     assert code(moe.moe_dispatch, s, 0x108, None, fake_plan(), 0x200, 0) == -3
     assert code(moe.moe_dispatch, s, 0x100, None, fake_plan(), 0x202, 0) == -3
     assert code(moe.moe_combine, s, 0x100, 0x204, fake_plan(), 0x300, 0) == -3

@@ -276,3 +276,70 @@ def test_hip_graph_replay_matches_eager(moe):
         assert to_host(layer.window).tobytes() == to_host(eager.window).tobytes(), rep
         assert to_host(layer.y).tobytes() == to_host(eager.y).tobytes(), rep
         assert to_host(layer.window).tobytes() == oracle.dispatch(w.X, ref.row_map, ref.window_rows).tobytes(), rep
+
+
+# --------------------------------------------------------------------------- several source ranks (Notify with M)
+
+def run_multi(moe, cfg, M, me, schedule, stride=0, seed=0):
+    """Plan / dispatch / combine of source rank `me` next to the blocks of the other sources."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    w = wl.make(cfg, seed=seed)
+    T, k, E, R = cfg.T, cfg.k, cfg.E, cfg.R
+    ref = oracle.plan_multi(w.K, M, me, E, R, stride)
+    rows = max(1, R * stride if stride else ref.window_rows)
+    print(f"[multi] T={T} E={E} R={R} me={me} schedule={schedule} stride={stride} rows={rows}", flush=True)
+    layer = MoeLayer(T, cfg.H, k, E, R, schedule=schedule, region_stride_rows=stride, rank_id=me,
+                     source_count=to_device(M), window_rows=rows)
+    fill = SENTINEL[np.dtype(np.uint16)]
+    layer.window.copy_(to_device(np.full(tuple(layer.window.shape), fill, np.uint16)))
+    xd = to_device(w.X) if T else torch.empty((1, cfg.H), dtype=torch.bfloat16, device="cuda")
+    kd = to_device(w.K) if T else torch.empty((1, k), dtype=torch.int32, device="cuda")
+    wd = to_device(w.W) if T else torch.empty((1, k), dtype=torch.float32, device="cuda")
+    if layer.schedule == moe.MOE_SCHEDULE_PREFILL:
+        moe.moe_plan(layer.shape, kd, layer.plan)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(layer.plan.row_map)[:T * k].reshape(T, k), ref.row_map), "row_map (plan only)"
+    layer.dispatch(xd, kd)
+    torch.cuda.synchronize()
+    p = layer.plan
+    assert np.array_equal(to_host(p.expert_count), ref.c_exp)
+    assert np.array_equal(to_host(p.rank_count), ref.c_rank)
+    assert np.array_equal(to_host(p.expert_offset), ref.expert_offset)
+    assert np.array_equal(to_host(p.region_base), ref.region_base)
+    assert np.array_equal(to_host(p.recv_count), ref.recv_count)
+    assert np.array_equal(to_host(p.recv_offset), ref.recv_offset)
+    assert np.array_equal(to_host(p.send_idx)[:T * k].reshape(T, k), ref.s)
+    assert np.array_equal(to_host(p.row_map)[:T * k].reshape(T, k), ref.row_map)
+    assert np.array_equal(to_host(p.status)[:2], ref.status)
+    ref_window = oracle.dispatch(w.X, ref.row_map, rows, fill=fill)        # other sources' rows stay untouched
+    assert to_host(layer.window)[:rows].tobytes() == ref_window.tobytes()
+    Yexp = oracle.expert_standin(ref_window, w.K, ref.row_map, w.scale)
+    layer.expert_out[:rows].copy_(to_device(Yexp))
+    layer.combine(wd)
+    torch.cuda.synchronize()
+    assert max_ulp(to_host(layer.y)[:T], oracle.combine(Yexp, w.W, ref.row_map)) <= 1
+    return ref
+
+
+@pytest.mark.parametrize("schedule", ["prefill", "decode"])
+def test_multi_source_notify(moe, schedule):
+    sch = moe.MOE_SCHEDULE_PREFILL if schedule == "prefill" else moe.MOE_SCHEDULE_DECODE
+    rng = np.random.default_rng(40)
+    for (T, H, k, E, R) in ((200, 256, 8, 64, 8), (77, 64, 4, 12, 4), (1000, 128, 8, 256, 32), (5, 64, 2, 8, 1)):
+        cfg = wl.Config("multi", T=T, H=H, k=k, E=E, R=R, seed=T)
+        M = rng.integers(0, 40, size=(R, E)).astype(np.int32)
+        for me in sorted({0, R // 2, R - 1}):
+            ref = run_multi(moe, cfg, M, me, sch, seed=T + me)
+            assert ref.window_rows > T * k or R == 1
+        # fixed stride, some regions overflowing
+        full = M.copy()
+        per_region = full.reshape(R, R, E // R).sum(axis=(0, 2)) + T * k // R
+        stride = int(np.sort(per_region)[R // 2])
+        ref = run_multi(moe, cfg, M, R - 1, sch, stride=stride, seed=T)
+    # no tokens on this rank, but other sources present
+    cfg = wl.Config("multi0", T=0, H=64, k=4, E=16, R=4)
+    run_multi(moe, cfg, rng.integers(0, 9, size=(4, 16)).astype(np.int32), 2, sch)
+    # zero matrix == single source
+    cfg = wl.Config("multiz", T=300, H=64, k=8, E=32, R=4, seed=9)
+    ref = run_multi(moe, cfg, np.zeros((4, 32), np.int32), 3, sch, seed=9)
+    assert np.array_equal(ref.expert_offset, oracle.plan(wl.make(cfg, seed=9).K, 32, 4).expert_offset)
