@@ -48,8 +48,9 @@ class Sets:
     """`n` disjoint buffer sets of one workload (rotating through them keeps small working sets
     out of the 256 MB Infinity Cache between steps)."""
 
-    def __init__(self, cfg, n, schedule=0):
+    def __init__(self, cfg, n, schedule=0, sources=1):
         import torch
+        import numpy as np
         import workloads as wl
         import paper_2605_06055_amd as moe
         from paper_2605_06055_amd.layer import MoeLayer, to_device
@@ -57,7 +58,17 @@ class Sets:
         self.layers, self.x, self.k, self.w = [], [], [], []
         for i in range(n):
             w = wl.make(cfg, seed=cfg.seed + i)
-            layer = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, dtype=cfg.dtype, schedule=schedule)
+            extra = {}
+            if sources > 1:
+                # the other source ranks route like this one: their counts are draws of the same workload
+                # (this rank is source rank R/2; rows of the other sources are never touched here)
+                M = np.stack([np.bincount(wl.make(cfg, seed=1000 + r).K.reshape(-1), minlength=cfg.E)
+                              if r < sources else np.zeros(cfg.E, np.int64) for r in range(cfg.R)]).astype(np.int32)
+                me = min(cfg.R // 2, sources - 1)
+                own = np.bincount(w.K.reshape(-1), minlength=cfg.E)
+                rows = int(M.sum() - M[me].sum() + own.sum())
+                extra = dict(source_count=to_device(M), rank_id=me, window_rows=rows)
+            layer = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, dtype=cfg.dtype, schedule=schedule, **extra)
             xd, kd, wd = to_device(w.X), to_device(w.K), to_device(w.W)
             layer.dispatch(xd, kd)
             layer.standin_expert(kd, to_device(w.scale))
@@ -99,9 +110,9 @@ def graph_time_ms(fn, n_calls, replays):
     return event_time_ms(lambda i: g.replay(), replays) / n_calls, g
 
 
-def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0):
+def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1):
     import paper_2605_06055_amd as moe
-    s = Sets(cfg, n_sets, schedule)
+    s = Sets(cfg, n_sets, schedule, sources)
     for i in range(warmup):
         s.step(i)
     if use_graph:
@@ -174,6 +185,9 @@ def main():
     ap.add_argument("--decode-sweep", action="store_true",
                     help="also time decode layers at the paper's Table 2 points: hidden 4096 and 7168, "
                          "batch 16..144 (HIP graph replay, cold buffers); printed to stderr and added to the JSON")
+    ap.add_argument("--multi-source", type=int, default=0, metavar="S",
+                    help="also time prefill T=4096 and decode T=128 as one of S source ranks (count matrix M given, "
+                         "windows hold the blocks of all S sources)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain elementwise copy of known size (512 MiB read + 512 MiB written, "
                          "torch.mul(src, 1, out=dst)) so that rocprofv3 --pmc counters can be scaled")
@@ -235,6 +249,17 @@ def main():
                          "cache": "cold: 20 disjoint buffer sets (660 MB) rotated so no step finds its lines in "
                                   "the 256 MB Infinity Cache",
                          "kernels": {k: round(v, 2) for k, v in d["kernels"].items()}}
+    if args.multi_source > 1:
+        S = args.multi_source
+        mp = measure(wl.CONFIGS["prefill"], args.steps, args.warmup, 1, sources=S)
+        md = measure(wl.CONFIGS["decode"], max(args.steps, 400), args.warmup, 20, use_graph=True, sources=S)
+        log(f"[prefill as one of {S} sources] {json.dumps(mp)}")
+        log(f"[decode as one of {S} sources, graph replay] {json.dumps(md)}")
+        out["multi_source"] = {"sources": S,
+                               "prefill_us_per_layer": round(mp["us_per_layer"], 2),
+                               "prefill_kernels": {k: round(v, 2) for k, v in mp["kernels"].items()},
+                               "decode_us_per_layer": round(md["us_per_layer"], 2),
+                               "decode_kernels": {k: round(v, 2) for k, v in md["kernels"].items()}}
     if args.decode_sweep:
         sweep = []
         for H in (4096, 7168):
