@@ -128,6 +128,27 @@ def dispatch(X: np.ndarray, row_map: np.ndarray, rows: int, fill=None) -> np.nda
     return window
 
 
+def dispatch_quant(X: np.ndarray, row_map: np.ndarray, rows: int, fill=0):
+    """Row-wise quantised dispatch: returns (window_q [rows,H] uint8 e4m3 codes, window_scale [rows] float32)."""
+    X = np.ascontiguousarray(X, dtype=np.uint16)
+    row_map = np.ascontiguousarray(row_map, dtype=np.int32)
+    T, H = X.shape
+    k = row_map.shape[1]
+    wq = np.full((rows, H), fill, np.uint8)
+    ws = np.full(rows, -1.0, np.float32)
+    rc = _load().moe_ref_dispatch_quant(ctypes.c_int32(T), ctypes.c_int32(H), ctypes.c_int32(k), _p(X), _p(row_map),
+                                        _p(wq), _p(ws))
+    assert rc == 0
+    return wq, ws
+
+
+def f32_to_e4m3(a: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    out = np.empty(a.shape, np.uint8)
+    _load().moe_ref_f32_to_e4m3(_p(a), _p(out), ctypes.c_int64(a.size))
+    return out
+
+
 def _combine(fn, Yexp, W, row_map):
     Yexp = np.ascontiguousarray(Yexp)
     W = np.ascontiguousarray(W, dtype=np.float32)

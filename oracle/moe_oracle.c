@@ -318,6 +318,60 @@ int moe_ref_expert_standin(int32_t T, int32_t H, int32_t k, int32_t dtype, const
   return 0;
 }
 
+/* ---- Row-wise quantised dispatch (Section 5.2, last sentences of "Prefill Dispatch") -------------------
+ *
+ * The paper only says that, with row-wise quantisation, each row's scale goes to a parallel scale tensor
+ * in the same row order; it gives no format.  Format chosen here (parity with the authors: unpinned):
+ *   payload  OCP FP8 E4M3 (1-4-3 bits, bias 7, largest finite 448, no infinities, NaN = S.1111.111);
+ *   amax   = max_h |x_h| over the row (as fp32);   scale = amax / 448   (stored, fp32, one rounding);
+ *   inv    = 448 / amax (fp32, one rounding);      q_h = e4m3(x_h * inv), nearest-even, saturating at 448;
+ *   amax == 0  ->  scale = 1, inv = 1.
+ * The token row is quantised once and the same bytes and scale go to each of its k destination rows.
+ */
+static uint8_t f32_to_e4m3_rne_sat(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  const uint8_t sign = (uint8_t)((u >> 24) & 0x80u);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint8_t)(sign | 0x7Fu);
+  const float a = fabsf(f);
+  if (a >= 448.0f) return (uint8_t)(sign | 0x7Eu);              /* saturate (also covers +-inf) */
+  if (a < 0x1p-6f) return (uint8_t)(sign | (uint8_t)nearbyintf(a * 0x1p9f)); /* subnormal grid 2^-9; 8 -> 2^-6 */
+  uint32_t v;
+  memcpy(&v, &a, 4);
+  const uint32_t lsb = (v >> 20) & 1u;                          /* keep 3 mantissa bits */
+  v += 0x7FFFFu + lsb;
+  v >>= 20;                                                     /* [exponent(8) | mantissa(3)], carry included */
+  const uint32_t code = v - ((127u - 7u) << 3);                 /* rebias 127 -> 7 */
+  return (uint8_t)(sign | (code > 0x7Eu ? 0x7Eu : code));
+}
+
+int moe_ref_dispatch_quant(int32_t T, int32_t H, int32_t k,
+                           const uint16_t *X,          /* [T, H] bf16 */
+                           const int32_t *row_map,     /* [T*k] */
+                           uint8_t *window_q,          /* [rows, H] e4m3; only mapped rows are written */
+                           float *window_scale)        /* [rows] */
+{
+  for (int32_t t = 0; t < T; ++t) {
+    const uint16_t *x = X + (size_t)t * (size_t)H;
+    float amax = 0.0f;
+    for (int32_t h = 0; h < H; ++h) amax = fmaxf(amax, fabsf(bf16_to_f32(x[h])));
+    const float scale = amax == 0.0f ? 1.0f : amax / 448.0f;
+    const float inv = amax == 0.0f ? 1.0f : 448.0f / amax;
+    for (int32_t j = 0; j < k; ++j) {
+      const int32_t p = row_map[(int64_t)t * k + j];
+      if (p < 0) continue;
+      uint8_t *q = window_q + (size_t)p * (size_t)H;
+      for (int32_t h = 0; h < H; ++h) q[h] = f32_to_e4m3_rne_sat(bf16_to_f32(x[h]) * inv);
+      window_scale[p] = scale;
+    }
+  }
+  return 0;
+}
+
+void moe_ref_f32_to_e4m3(const float *in, uint8_t *out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = f32_to_e4m3_rne_sat(in[i]);
+}
+
 /* storage conversions, exported so tests can pin them against an independent library */
 void moe_ref_f32_to_bf16(const float *in, uint16_t *out, int64_t n) {
   for (int64_t i = 0; i < n; ++i) out[i] = f32_to_bf16_rne(in[i]);

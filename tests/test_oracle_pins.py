@@ -352,7 +352,55 @@ def check_multi_against_library(seed=6):
         assert np.array_equal(pf.row_map.reshape(-1), np.where(dropped, -1, wantf)) and pf.status[1] == dropped.sum()
 
 
-PINS = [check_golden, check_golden_multi, check_multi_against_library, check_plan_against_library, check_masked_and_invalid, check_fixed_stride, check_dispatch,
+def check_quantised(seed=7):
+    """Row-wise quantised dispatch: hand-worked codes, torch's float8_e4m3fn conversion as the library step,
+    exact scales, and the dequantisation error bound of the format."""
+    import torch
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "worked_example.json")))
+    X = bf16(g["X"])
+    pl = oracle.plan(np.asarray(g["K"], np.int32), g["E"], g["R"])
+    wq, ws = oracle.dispatch_quant(X, pl.row_map, pl.window_rows)
+    tok = np.asarray(g["tight"]["window_token"])
+    assert wq.tolist() == np.asarray(g["quantised"]["q_token"])[tok].tolist()
+    want_scale = (np.asarray(g["quantised"]["scale_numerator"], np.float32) / np.float32(448))[tok]
+    assert np.array_equal(ws, want_scale)
+    # conversion against an independent implementation, including ties, subnormals and saturation
+    rng = np.random.default_rng(seed)
+    f = np.concatenate([rng.uniform(-448, 448, 100000), rng.uniform(-0.05, 0.05, 20000),
+                        [0.0, -0.0, 448.0, -448.0, 2 ** -9, 2 ** -10, 1.5 * 2 ** -9, 2.5 * 2 ** -9, 2 ** -6, 336.0, 352.0,
+                         17.0, 19.0, 447.99997]]).astype(np.float32)
+    want = torch.from_numpy(f).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(oracle.f32_to_e4m3(f), want)
+    assert oracle.f32_to_e4m3(np.array([1e9, -1e9, np.inf, 448.00003], np.float32)).tolist() == [0x7E, 0xFE, 0x7E, 0x7E]
+    # a random batch: same arithmetic spelled with numpy fp32 ops and torch's conversion
+    T, H, k, E, R = 19, 48, 3, 6, 3
+    Xf = (rng.standard_normal((T, H)) * np.exp(rng.uniform(-3, 3, (T, 1)))).astype(np.float32)
+    Xf[5] = 0.0                                                   # an all-zero row: scale 1, codes 0
+    Xb = bf16(Xf)
+    x = unbf16(Xb)
+    K = wl.random_routing(rng, T, k, E, p_masked=0.1)
+    pl = oracle.plan(K, E, R)
+    wq, ws = oracle.dispatch_quant(Xb, pl.row_map, pl.window_rows + 2, fill=0xAA)
+    amax = np.abs(x).max(axis=1)
+    scale = np.where(amax == 0, np.float32(1), amax / np.float32(448)).astype(np.float32)
+    inv = np.where(amax == 0, np.float32(1), np.float32(448) / np.where(amax == 0, 1, amax)).astype(np.float32)
+    q = torch.from_numpy((x * inv[:, None]).astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    q = np.where(np.abs(x * inv[:, None]) >= 448, np.where(x < 0, 0xFE, 0x7E), q).astype(np.uint8)   # saturate, not NaN
+    for i, p in enumerate(pl.row_map.reshape(-1)):
+        if p >= 0:
+            assert np.array_equal(wq[p], q[i // k]) and ws[p] == scale[i // k]
+    untouched = np.setdiff1d(np.arange(wq.shape[0]), pl.row_map.reshape(-1))
+    assert np.all(wq[untouched] == 0xAA) and np.all(ws[untouched] == -1.0)
+    deq = torch.from_numpy(wq[:pl.window_rows]).view(torch.float8_e4m3fn).float().numpy() * ws[:pl.window_rows, None]
+    src = np.empty(pl.window_rows, np.int64)
+    for i, p in enumerate(pl.row_map.reshape(-1)):
+        if p >= 0:
+            src[p] = i // k
+    # half a unit in the last place of the top binade (16 of 448) plus the roundings of scale and inv
+    assert np.all(np.abs(deq - x[src]) <= amax[src][:, None] * (16.0 / 448 + 1e-6))
+
+
+PINS = [check_golden, check_golden_multi, check_quantised, check_multi_against_library, check_plan_against_library, check_masked_and_invalid, check_fixed_stride, check_dispatch,
         check_combine, check_accumulation_order, check_rounding]
 
 
@@ -441,6 +489,11 @@ MUTANTS["multi_sources_reversed"] = ("      for (int32_t r = 0; r < R; ++r) {\n 
 MUTANTS["multi_offset_is_block_start"] = ("expert_offset[e] = o_all[(int64_t)e * R + me];", "expert_offset[e] = recv_offset[e];")
 MUTANTS["multi_stride_ignored"] = ("    if (region_stride_rows > 0) run = (int32_t)((int64_t)d * region_stride_rows);\n    region_base[d] = run;",
                                    "    region_base[d] = run;")
+MUTANTS["quant_truncates"] = ("  v += 0x7FFFFu + lsb;\n  v >>= 20;", "  v += 0u * lsb;\n  v >>= 20;")
+MUTANTS["quant_half_up"] = ("  v += 0x7FFFFu + lsb;\n  v >>= 20;", "  v += 0x80000u + 0u * lsb;\n  v >>= 20;")
+MUTANTS["quant_scale_is_inverse"] = ("      window_scale[p] = scale;", "      window_scale[p] = inv;")
+MUTANTS["quant_amax_signed"] = ("amax = fmaxf(amax, fabsf(bf16_to_f32(x[h])));", "amax = fmaxf(amax, bf16_to_f32(x[h]));")
+MUTANTS["quant_bias_off_by_one"] = ("const uint32_t code = v - ((127u - 7u) << 3);", "const uint32_t code = v - ((127u - 8u) << 3);")
 # an unstable but otherwise valid placement: reverse order inside each expert block
 MUTANTS["s_not_stable"] = ("    row_map[i] = row;\n", "    row_map[i] = expert_offset[e] + (c_exp[e] - 1 - s[i]);\n")
 
