@@ -48,7 +48,7 @@ class Sets:
     """`n` disjoint buffer sets of one workload (rotating through them keeps small working sets
     out of the 256 MB Infinity Cache between steps)."""
 
-    def __init__(self, cfg, n, schedule=0, sources=1):
+    def __init__(self, cfg, n, schedule=0, sources=1, quant=False):
         import torch
         import numpy as np
         import workloads as wl
@@ -56,6 +56,7 @@ class Sets:
         from paper_2605_06055_amd.layer import MoeLayer, to_device
         self.cfg, self.n, self.moe = cfg, n, moe
         self.layers, self.x, self.k, self.w = [], [], [], []
+        self.quant, self.wq, self.ws = quant, [], []
         for i in range(n):
             w = wl.make(cfg, seed=cfg.seed + i)
             extra = {}
@@ -73,13 +74,21 @@ class Sets:
             layer.dispatch(xd, kd)
             layer.standin_expert(kd, to_device(w.scale))
             self.layers.append(layer), self.x.append(xd), self.k.append(kd), self.w.append(wd)
+            if quant:     # e4m3 codes and row scales replace the bf16 window on the dispatch side
+                self.wq.append(torch.empty((layer.rows, cfg.H), dtype=torch.uint8, device="cuda"))
+                self.ws.append(torch.empty((layer.rows,), dtype=torch.float32, device="cuda"))
         torch.cuda.synchronize()
         self.schedule = self.layers[0].schedule
 
     def step(self, i):
         j = i % self.n
         L = self.layers[j]
-        L.dispatch(self.x[j], self.k[j])
+        if self.quant:
+            if L.schedule == self.moe.MOE_SCHEDULE_PREFILL:
+                self.moe.moe_plan(L.shape, self.k[j], L._plan_struct)
+            self.dispatch_only(i)
+        else:
+            L.dispatch(self.x[j], self.k[j])
         L.combine(self.w[j])
 
     def plan_only(self, i):
@@ -90,7 +99,10 @@ class Sets:
     def dispatch_only(self, i):
         j = i % self.n
         L = self.layers[j]
-        self.moe.moe_dispatch(L.shape, self.x[j], self.k[j], L._plan_struct, L.window)
+        if self.quant:
+            self.moe.moe_dispatch_quant(L.shape, self.x[j], self.k[j], L._plan_struct, self.wq[j], self.ws[j])
+        else:
+            self.moe.moe_dispatch(L.shape, self.x[j], self.k[j], L._plan_struct, L.window)
 
     def combine_only(self, i):
         j = i % self.n
@@ -110,9 +122,9 @@ def graph_time_ms(fn, n_calls, replays):
     return event_time_ms(lambda i: g.replay(), replays) / n_calls, g
 
 
-def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1):
+def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1, quant=False):
     import paper_2605_06055_amd as moe
-    s = Sets(cfg, n_sets, schedule, sources)
+    s = Sets(cfg, n_sets, schedule, sources, quant)
     for i in range(warmup):
         s.step(i)
     if use_graph:
@@ -185,6 +197,9 @@ def main():
     ap.add_argument("--decode-sweep", action="store_true",
                     help="also time decode layers at the paper's Table 2 points: hidden 4096 and 7168, "
                          "batch 16..144 (HIP graph replay, cold buffers); printed to stderr and added to the JSON")
+    ap.add_argument("--quant", action="store_true",
+                    help="also time prefill T=4096 and decode T=128 with the row-wise quantised dispatch "
+                         "(FP8 E4M3 codes + fp32 row scales on the dispatch side, bf16 combine)")
     ap.add_argument("--multi-source", type=int, default=0, metavar="S",
                     help="also time prefill T=4096 and decode T=128 as one of S source ranks (count matrix M given, "
                          "windows hold the blocks of all S sources)")
@@ -249,6 +264,25 @@ def main():
                          "cache": "cold: 20 disjoint buffer sets (660 MB) rotated so no step finds its lines in "
                                   "the 256 MB Infinity Cache",
                          "kernels": {k: round(v, 2) for k, v in d["kernels"].items()}}
+    if args.quant:
+        pc, dc = wl.CONFIGS["prefill"], wl.CONFIGS["decode"]
+        qp = measure(pc, args.steps, args.warmup, 1, quant=True)
+        qd = measure(dc, max(args.steps, 400), args.warmup, 20, use_graph=True, quant=True)
+        log(f"[prefill, quantised dispatch] {json.dumps(qp)}")
+        log(f"[decode, quantised dispatch, graph replay] {json.dumps(qd)}")
+
+        def qbytes(c):      # X read once as bf16; codes (1 byte) and a 4-byte scale written per routed row
+            return c.T * c.H * 2 + c.N * (c.H + 4)
+        out["quantised_dispatch"] = {
+            "format": "OCP FP8 E4M3 codes + fp32 scale per row (amax/448)",
+            "prefill": {"us_per_layer": round(qp["us_per_layer"], 2),
+                        "dispatch_us": round(qp["kernels"]["dispatch_us"], 2), "dispatch_bytes": qbytes(pc),
+                        "dispatch_GBps": round(qbytes(pc) / qp["kernels"]["dispatch_us"] / 1e3, 1),
+                        "combine_us": round(qp["kernels"]["combine_us"], 2)},
+            "decode": {"us_per_layer": round(qd["us_per_layer"], 2),
+                       "dispatch_us": round(qd["kernels"]["dispatch_us"], 2), "dispatch_bytes": qbytes(dc),
+                       "dispatch_GBps": round(qbytes(dc) / qd["kernels"]["dispatch_us"] / 1e3, 1),
+                       "combine_us": round(qd["kernels"]["combine_us"], 2)}}
     if args.multi_source > 1:
         S = args.multi_source
         mp = measure(wl.CONFIGS["prefill"], args.steps, args.warmup, 1, sources=S)

@@ -136,6 +136,17 @@ int moe_plan(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, 
 int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx, moe_plan_t *plan,
                  void *window, void *stream);
 
+/* Row-wise quantised dispatch (paper, Section 5.2, end of "Prefill Dispatch": with row-wise quantisation the
+ * scale values go to a parallel scale tensor in the same row order; the "quant" rows of Table 2).  The paper
+ * names no format; this library's format is OCP FP8 E4M3 codes plus one float32 scale per row:
+ *   amax = max |x| over the token row, scale = amax / 448, code = e4m3(x * (448 / amax)) rounded to nearest
+ *   even; an all-zero row has scale 1.  Every destination row of a token receives the same codes and scale.
+ *   shape->dtype must be MOE_DTYPE_BF16 (type of x) and H <= 32768; schedules and plan as for moe_dispatch.
+ *   window_q     : device, [moe_window_rows, H] bytes; only rows some branch maps to are written.
+ *   window_scale : device, float32 [moe_window_rows]; same rows. */
+int moe_dispatch_quant(const moe_shape *shape, const void *x, const int32_t *topk_idx, moe_plan_t *plan,
+                       void *window_q, float *window_scale, void *stream);
+
 /* Combine (paper, Section 5.2 "Prefill Combine" / Section 5.3 "Decode Combine"; second loop of
  * Algorithms 1 and 2): Y[t,:] = sum_j W[t,j] * expert_out[row_map[t,j], :].
  *   Accumulation is fp32 from +0 in ascending j with one fused multiply-add per placed branch and a single

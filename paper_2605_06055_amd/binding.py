@@ -70,12 +70,13 @@ def load_library():
         lib.moe_plan.argtypes = [shp, vp, plp, vp]
         lib.moe_dispatch.argtypes = [shp, vp, vp, plp, vp, vp]
         lib.moe_combine.argtypes = [shp, vp, vp, plp, vp, vp]
+        lib.moe_dispatch_quant.argtypes = [shp, vp, vp, plp, vp, vp, vp]
         lib.moe_strerror.argtypes = [ctypes.c_int]
         lib.moe_strerror.restype = ctypes.c_char_p
         lib.moe_last_launch_error.argtypes = []
         lib.moe_last_launch_error.restype = ctypes.c_char_p
         for f in ("moe_workspace_bytes", "moe_window_rows", "moe_resolve_schedule", "moe_plan", "moe_dispatch",
-                  "moe_combine"):
+                  "moe_dispatch_quant", "moe_combine"):
             getattr(lib, f).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -165,6 +166,13 @@ def moe_dispatch(shape: MoeShape, x, topk_idx, plan, window, stream=None) -> Non
     ps = _plan_struct(plan)
     _check(load_library().moe_dispatch(ctypes.byref(shape), _ptr(x), _ptr(topk_idx), ctypes.byref(ps),
                                        _ptr(window), _stream(stream)), "moe_dispatch")
+
+
+def moe_dispatch_quant(shape: MoeShape, x, topk_idx, plan, window_q, window_scale, stream=None) -> None:
+    ps = _plan_struct(plan)
+    _check(load_library().moe_dispatch_quant(ctypes.byref(shape), _ptr(x), _ptr(topk_idx), ctypes.byref(ps),
+                                             _ptr(window_q), _ptr(window_scale), _stream(stream)),
+           "moe_dispatch_quant")
 
 
 def moe_combine(shape: MoeShape, expert_out, topk_w, plan, y, stream=None) -> None:

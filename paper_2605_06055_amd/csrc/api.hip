@@ -160,6 +160,26 @@ int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx,
                               : launch_dispatch(d, x, v, window, s));
 }
 
+int moe_dispatch_quant(const moe_shape *shape, const void *x, const int32_t *topk_idx, moe_plan_t *plan,
+                       void *window_q, float *window_scale, void *stream) {
+  Dims d;
+  PlanView v;
+  int rc = check_shape(shape, &d);
+  if (rc != MOE_OK) return rc;
+  if (shape->dtype != MOE_DTYPE_BF16 || d.H16 > 4096) return MOE_ERR_SHAPE;
+  const bool decode = resolve(shape) == MOE_SCHEDULE_DECODE;
+  if (!plan) return MOE_ERR_NULL;
+  if (d.T > 0 && (!x || !window_q || !window_scale || (decode && !topk_idx))) return MOE_ERR_NULL;
+  rc = check_plan(plan, decode, &v);
+  if (rc != MOE_OK) return rc;
+  if (!aligned16(x) || !aligned16(window_q) || !aligned16(window_scale) || (decode && !aligned16(topk_idx)))
+    return MOE_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  if (d.T == 0) return decode ? launch_status(launch_plan_empty(d, v, s)) : MOE_OK;
+  return launch_status(decode ? launch_decode_dispatch_quant(d, x, topk_idx, v, window_q, window_scale, s)
+                              : launch_dispatch_quant(d, x, v, window_q, window_scale, s));
+}
+
 int moe_combine(const moe_shape *shape, const void *expert_out, const float *topk_w, const moe_plan_t *plan,
                 void *y, void *stream) {
   Dims d;

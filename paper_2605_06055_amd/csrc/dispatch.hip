@@ -8,6 +8,7 @@
 #include "device_utils.h"
 #include "launch.h"
 #include "plan_tables.h"
+#include "quant.h"
 
 namespace moe_rbf {
 
@@ -88,10 +89,13 @@ __device__ __forceinline__ void decode_tables_block(const int32_t *__restrict__ 
   write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, misc[0], misc + 1);
 }
 
-template <int BLOCK, int V>
+// QUANT: the workgroup holds a whole row (chunks == 1), quantises it once and fans the codes and the
+// row's scale out instead of the bf16 payload.
+template <int BLOCK, int V, bool QUANT>
 __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__restrict__ X,
                                                                 const int32_t *__restrict__ K,
-                                                                u32x4 *__restrict__ window, Dims d, PlanView p,
+                                                                void *__restrict__ window_any,
+                                                                float *__restrict__ window_scale, Dims d, PlanView p,
                                                                 int chunks) {
   extern __shared__ int lds[];                                  // tables workgroup; several-sources prefix tables
   __shared__ int part[(BLOCK / kWave) * kSlotBatch];            // per-wave packed counts of a slot batch
@@ -113,6 +117,15 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
   for (int x = 0; x < V; ++x) {
     const int col = col0 + x * BLOCK;
     v[x] = col < d.H16 ? load_stream(src + col) : u32x4{0u, 0u, 0u, 0u};
+  }
+  u32x2 q[V];
+  float scale = 0.0f;
+  if (QUANT) {
+    __shared__ float red[BLOCK / kWave];
+    bool has[V];
+#pragma unroll
+    for (int x = 0; x < V; ++x) has[x] = col0 + x * BLOCK < d.H16;
+    scale = quantise_row<BLOCK, V>(v, has, q, red);
   }
   constexpr int kIds = 4;        // ids per thread kept in registers (first kIds passes over K)
   int id[kIds];
@@ -200,12 +213,59 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
     for (int u = 0; u < nb; ++u) {
       const int r = __builtin_amdgcn_readlane(row, u);
       if (r < 0) continue;
-      u32x4 *dst = window + (size_t)r * (size_t)d.H16;
+      if (QUANT) {
+        u32x2 *dst = (u32x2 *)window_any + (size_t)r * (size_t)d.H16;    // H bytes per row = H16 8-byte units
 #pragma unroll
-      for (int x = 0; x < V; ++x) {
-        const int col = col0 + x * BLOCK;
-        if (col < d.H16) store_stream(dst + col, v[x]);
+        for (int x = 0; x < V; ++x) {
+          const int col = col0 + x * BLOCK;
+          if (col < d.H16) __builtin_nontemporal_store(q[x], dst + col);
+        }
+        if (tid == 0) window_scale[r] = scale;
+      } else {
+        u32x4 *dst = (u32x4 *)window_any + (size_t)r * (size_t)d.H16;
+#pragma unroll
+        for (int x = 0; x < V; ++x) {
+          const int col = col0 + x * BLOCK;
+          if (col < d.H16) store_stream(dst + col, v[x]);
+        }
       }
+    }
+  }
+}
+
+// Quantised dispatch with the row map from moe_plan: one workgroup per token holds the whole row,
+// quantises it once and stores the codes and the scale to the k destination rows.
+template <int BLOCK, int V>
+__global__ __launch_bounds__(BLOCK) void dispatch_quant_rows_kernel(const u32x4 *__restrict__ X,
+                                                                    const int32_t *__restrict__ row_map,
+                                                                    u32x2 *__restrict__ window_q,
+                                                                    float *__restrict__ window_scale, int k, int H16) {
+  __shared__ float red[BLOCK / kWave];
+  const int t = blockIdx.x, tid = threadIdx.x;
+  const u32x4 *src = X + (size_t)t * (size_t)H16;
+  u32x4 v[V];
+  bool has[V];
+#pragma unroll
+  for (int x = 0; x < V; ++x) {
+    const int col = tid + x * BLOCK;
+    has[x] = col < H16;
+    v[x] = has[x] ? load_stream(src + col) : u32x4{0u, 0u, 0u, 0u};
+  }
+  u32x2 q[V];
+  const float scale = quantise_row<BLOCK, V>(v, has, q, red);
+  const int32_t *rows = row_map + (size_t)t * k;
+  for (int j0 = 0; j0 < k; j0 += 8) {
+    int row[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) row[u] = j0 + u < k ? uniform(rows[j0 + u]) : -1;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (row[u] < 0) continue;
+      u32x2 *dst = window_q + (size_t)row[u] * (size_t)H16;
+#pragma unroll
+      for (int x = 0; x < V; ++x)
+        if (has[x]) __builtin_nontemporal_store(q[x], dst + tid + x * BLOCK);
+      if (tid == 0) window_scale[row[u]] = scale;
     }
   }
 }
@@ -235,8 +295,35 @@ hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K
   constexpr int B = MOE_DECODE_BLOCK, V = MOE_DECODE_VEC;
   const int chunks = (d.H16 + B * V - 1) / (B * V);
   const size_t lds = (size_t)(4 * d.E + 1 + 2) * sizeof(int);
-  return launch(decode_dispatch_kernel<B, V>, dim3((unsigned)d.T * (unsigned)chunks + 1u), dim3(B), lds, s,
-                (const u32x4 *)x, K, (u32x4 *)window, d, p, chunks);
+  return launch(decode_dispatch_kernel<B, V, false>, dim3((unsigned)d.T * (unsigned)chunks + 1u), dim3(B), lds, s,
+                (const u32x4 *)x, K, window, (float *)nullptr, d, p, chunks);
+}
+
+// Whole-row workgroup shapes for the quantised kernels: (threads, vectors per thread) covering H16 <= 4096.
+#define MOE_QUANT_SHAPES(GO) \
+  if (d.H16 <= 256) GO(256, 1);  \
+  else if (d.H16 <= 512) GO(512, 1);  \
+  else if (d.H16 <= 1024) GO(1024, 1); \
+  else if (d.H16 <= 2048) GO(1024, 2); \
+  else GO(1024, 4)
+
+hipError_t launch_dispatch_quant(const Dims &d, const void *x, const PlanView &p, void *window_q, float *window_scale,
+                                 hipStream_t s) {
+#define GO(B_, V_)                                                                                         \
+  return launch(dispatch_quant_rows_kernel<B_, V_>, dim3((unsigned)d.T), dim3(B_), 0, s, (const u32x4 *)x, \
+                (const int32_t *)p.row_map, (u32x2 *)window_q, window_scale, d.k, d.H16)
+  MOE_QUANT_SHAPES(GO);
+#undef GO
+}
+
+hipError_t launch_decode_dispatch_quant(const Dims &d, const void *x, const int32_t *K, const PlanView &p,
+                                        void *window_q, float *window_scale, hipStream_t s) {
+  const size_t lds = (size_t)(4 * d.E + 1 + 2) * sizeof(int);
+#define GO(B_, V_)                                                                                                 \
+  return launch(decode_dispatch_kernel<B_, V_, true>, dim3((unsigned)d.T + 1u), dim3(B_), lds, s, (const u32x4 *)x, \
+                K, window_q, window_scale, d, p, 1)
+  MOE_QUANT_SHAPES(GO);
+#undef GO
 }
 
 }  // namespace moe_rbf

@@ -40,6 +40,10 @@ hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32
 hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void *window, hipStream_t s);
 hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K, const PlanView &p, void *window,
                                   hipStream_t s);
+hipError_t launch_dispatch_quant(const Dims &d, const void *x, const PlanView &p, void *window_q, float *window_scale,
+                                 hipStream_t s);
+hipError_t launch_decode_dispatch_quant(const Dims &d, const void *x, const int32_t *K, const PlanView &p,
+                                        void *window_q, float *window_scale, hipStream_t s);
 hipError_t launch_combine(const Dims &d, const void *expert_out, const float *W, const PlanView &p, void *y,
                           hipStream_t s);
 

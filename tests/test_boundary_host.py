@@ -139,6 +139,17 @@ def test_empty_prefill_dispatch_and_combine_are_noops():
     moe.moe_combine(s, None, None, fake_plan(), None, 0)
 
 
+def test_quantised_dispatch_validation():
+    s = shape(**PRE)
+    assert code(moe.moe_dispatch_quant, shape(dtype=moe.MOE_DTYPE_F32, **PRE), 0x100, None, fake_plan(), 0x200,
+                0x300, 0) == -2                                                     # x must be bf16
+    assert code(moe.moe_dispatch_quant, shape(H=40000, **PRE), 0x100, None, fake_plan(), 0x200, 0x300, 0) == -2
+    assert code(moe.moe_dispatch_quant, s, 0x100, None, fake_plan(), None, 0x300, 0) == -1
+    assert code(moe.moe_dispatch_quant, s, 0x100, None, fake_plan(), 0x200, None, 0) == -1
+    assert code(moe.moe_dispatch_quant, s, 0x100, None, fake_plan(), 0x204, 0x300, 0) == -3
+    assert code(moe.moe_dispatch_quant, shape(), 0x100, None, fake_plan(), 0x200, 0x300, 0) == -1    # decode needs ids
+
+
 def test_strerror():
     texts = {moe.moe_strerror(c) for c in range(0, -7, -1)}
     assert len(texts) == 7 and moe.moe_strerror(-99) == "unknown status"

@@ -343,3 +343,54 @@ def test_multi_source_notify(moe, schedule):
     cfg = wl.Config("multiz", T=300, H=64, k=8, E=32, R=4, seed=9)
     ref = run_multi(moe, cfg, np.zeros((4, 32), np.int32), 3, sch, seed=9)
     assert np.array_equal(ref.expert_offset, oracle.plan(wl.make(cfg, seed=9).K, 32, 4).expert_offset)
+
+
+# --------------------------------------------------------------------------- row-wise quantised dispatch
+
+def run_quant(moe, cfg, schedule, stride=0, seed=0, scale_rows=None):
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    w = wl.make(cfg, seed=seed)
+    X = w.X.copy()
+    if scale_rows is not None:                       # per-row magnitudes spread over many binades
+        f = wl.bf16_bits_to_f32(X) * scale_rows[:, None]
+        X = wl.f32_to_bf16_bits(f.astype(np.float32))
+    T, H, k, E, R = cfg.T, cfg.H, cfg.k, cfg.E, cfg.R
+    ref = oracle.plan(w.K, E, R, stride)
+    layer = MoeLayer(T, H, k, E, R, schedule=schedule, region_stride_rows=stride)
+    rows = layer.rows
+    print(f"[quant] T={T} H={H} k={k} E={E} schedule={schedule} stride={stride}", flush=True)
+    wq = torch.full((max(rows, 1), H), 0xAA, dtype=torch.uint8, device="cuda")
+    ws = torch.full((max(rows, 1),), -1.0, dtype=torch.float32, device="cuda")
+    xd, kd = to_device(X), to_device(w.K)
+    if layer.schedule == moe.MOE_SCHEDULE_PREFILL:
+        moe.moe_plan(layer.shape, kd, layer.plan)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(layer.plan.row_map)[:T * k].reshape(T, k), ref.row_map)
+    moe.moe_dispatch_quant(layer.shape, xd, kd, layer.plan, wq, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(layer.plan.row_map)[:T * k].reshape(T, k), ref.row_map)
+    assert np.array_equal(to_host(layer.plan.expert_count), ref.c_exp)
+    ref_q, ref_s = oracle.dispatch_quant(X, ref.row_map, max(rows, 1), fill=0xAA)
+    got_q, got_s = wq.cpu().numpy(), ws.cpu().numpy()
+    assert got_s.tobytes() == ref_s.tobytes(), "row scales"
+    bad = np.count_nonzero(got_q != ref_q)
+    assert bad == 0, f"{bad} of {got_q.size} fp8 codes differ"
+
+
+@pytest.mark.parametrize("schedule", ["prefill", "decode"])
+def test_quantised_dispatch(moe, schedule):
+    sch = moe.MOE_SCHEDULE_PREFILL if schedule == "prefill" else moe.MOE_SCHEDULE_DECODE
+    rng = np.random.default_rng(50)
+    for (T, H, k, E, R) in ((128, 7168, 8, 256, 32), (100, 4096, 8, 128, 16), (61, 1032, 3, 12, 4), (200, 64, 8, 32, 4),
+                            (9, 16384, 4, 8, 2), (33, 30000 // 8 * 8, 2, 4, 1)):
+        cfg = wl.Config("quant", T=T, H=H, k=k, E=E, R=R, seed=T)
+        run_quant(moe, cfg, sch, seed=T, scale_rows=np.exp(rng.uniform(-8, 8, T)).astype(np.float32))
+    cfg = wl.Config("quant", T=64, H=512, k=4, E=16, R=4, seed=3)
+    zero = np.ones(64, np.float32)
+    zero[::5] = 0.0                                   # all-zero rows: scale 1, codes 0
+    run_quant(moe, cfg, sch, seed=3, scale_rows=zero)
+    run_quant(moe, cfg, sch, stride=70, seed=4)       # fixed stride with overflow
+
+
+def test_quantised_dispatch_full_prefill(moe):
+    run_quant(moe, wl.CONFIGS["prefill"], moe.MOE_SCHEDULE_AUTO)
