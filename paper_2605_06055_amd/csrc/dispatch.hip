@@ -55,8 +55,9 @@ __global__ __launch_bounds__(BLOCK) void dispatch_slices_kernel(const u32x4 *__r
 // (lo = 0 and base = 0 for tight windows; lo = first expert of e's rank and base = rank*stride otherwise).
 // Both terms are plain counts over the <= 8192 routing ids of the batch, so a payload workgroup gets
 // them with compares on the ids it holds in registers, wave ballots (the counts land in scalar
-// registers) and one LDS exchange between its waves: no histogram, no scan, one barrier.  The two counts of a slot travel packed in
-// one word (low 16 bits: ids below e; high 16 bits: equal ids in front of the branch).
+// registers) and one LDS exchange between its waves: no histogram, no scan, one barrier.  The two
+// counts of a slot travel packed in one word (low 16 bits: ids below e; high 16 bits: equal ids in
+// front of the branch).
 // One extra workgroup (the last) builds the histogram and writes the tables for combine and the experts.
 
 constexpr int kSlotBatch = 8;     // slots of a token ranked together
@@ -118,6 +119,13 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
     const int col = col0 + x * BLOCK;
     v[x] = col < d.H16 ? load_stream(src + col) : u32x4{0u, 0u, 0u, 0u};
   }
+  constexpr int kIds = 4;        // ids per thread kept in registers (first kIds passes over K)
+  int id[kIds];
+#pragma unroll
+  for (int u = 0; u < kIds; ++u) {
+    const int i = u * BLOCK + tid;
+    id[u] = i < d.N ? K[i] : -1;
+  }
   u32x2 q[V];
   float scale = 0.0f;
   if (QUANT) {
@@ -126,13 +134,6 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
 #pragma unroll
     for (int x = 0; x < V; ++x) has[x] = col0 + x * BLOCK < d.H16;
     scale = quantise_row<BLOCK, V>(v, has, q, red);
-  }
-  constexpr int kIds = 4;        // ids per thread kept in registers (first kIds passes over K)
-  int id[kIds];
-#pragma unroll
-  for (int u = 0; u < kIds; ++u) {
-    const int i = u * BLOCK + tid;
-    id[u] = i < d.N ? K[i] : -1;
   }
 
   // several source ranks: rows of the other sources in front of a slot's sub-block =

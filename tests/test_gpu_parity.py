@@ -394,3 +394,41 @@ def test_quantised_dispatch(moe, schedule):
 
 def test_quantised_dispatch_full_prefill(moe):
     run_quant(moe, wl.CONFIGS["prefill"], moe.MOE_SCHEDULE_AUTO)
+
+
+# --------------------------------------------------------------------------- seeded shape fuzz
+
+def test_seeded_random_shapes(moe):
+    """Forty seeded shapes over both schedules: odd sizes, masked / invalid / duplicate ids, fixed strides,
+    several source ranks, fp32 and bf16 storage, routing degrees up to 100 and E up to the limit."""
+    rng = np.random.default_rng(2024)
+    from paper_2605_06055_amd.layer import to_device
+    for case in range(40):
+        R = int(rng.choice([1, 2, 3, 4, 8, 16, 32]))
+        Er = int(rng.choice([1, 2, 3, 8, 32]))
+        E = min(R * Er, 1024)
+        R = E // Er
+        k = int(rng.choice([1, 2, 3, 8, 9, 16, 64, 100]))
+        decode = bool(rng.integers(0, 2))
+        T = int(rng.integers(1, max(2, 8192 // k))) if decode else int(rng.integers(1, 3000))
+        if decode and T * k > 8192:
+            T = 8192 // k
+        dtype = np.uint16 if rng.random() < 0.7 else np.float32
+        H = int(rng.integers(1, 300)) * (8 if dtype == np.uint16 else 4)
+        K = wl.random_routing(rng, T, k, E, distinct=bool(rng.integers(0, 2)), p_masked=float(rng.choice([0, 0.1])),
+                              p_invalid=float(rng.choice([0, 0.05])))
+        sch = moe.MOE_SCHEDULE_DECODE if decode else moe.MOE_SCHEDULE_PREFILL
+        tight = oracle.plan(K, E, R)
+        stride = 0
+        if rng.random() < 0.3:
+            stride = max(1, int(tight.c_rank.max() * rng.uniform(0.6, 1.3)))
+        _case(moe, K, E, R, sch, H=H, stride=stride, dtype=dtype, seed=case, label=f"fuzz {case}")
+
+
+def test_decode_schedule_limits(moe):
+    """Largest batch the fused decode kernel accepts (8192 branches) with the largest expert count."""
+    rng = np.random.default_rng(77)
+    K = wl.random_routing(rng, 1024, 8, 1024, distinct=True)
+    _case(moe, K, 1024, 128, moe.MOE_SCHEDULE_DECODE, H=64, label="decode N=8192 E=1024")
+    K = wl.random_routing(rng, 64, 128, 1024)          # k = 128 with duplicates
+    _case(moe, K, 1024, 1024, moe.MOE_SCHEDULE_DECODE, H=8, label="decode k=128 E=R=1024")
