@@ -89,8 +89,9 @@ __global__ __launch_bounds__(BLOCK) void combine_rows_kernel(const u32x4 *__rest
   const int c = blockIdx.x - t * chunks;
   const int col = c * BLOCK + threadIdx.x;
   if (col >= H16) return;
-  const int32_t *rows = row_map + (size_t)t * k;
-  const float *w = W + (size_t)t * k;
+  // both arrays are 16-byte aligned (checked at the boundary): lets the scalar loads be wide
+  const int32_t *rows = (const int32_t *)__builtin_assume_aligned(row_map, 16) + (size_t)t * k;
+  const float *w = (const float *)__builtin_assume_aligned(W, 16) + (size_t)t * k;
   const u32x4 *base = Yexp + col;
   Acc<DT> acc;
   acc.zero();
