@@ -155,6 +155,29 @@ def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1, 
     return res
 
 
+def copy_ceiling():
+    """Practical streaming roofs of the box, for context next to the 8 TB/s peak: a device-to-device
+    memcpy of 1 GiB and the library's own 16-byte copy (dispatch with k = 1 and one expert is a plain
+    row copy: 0.94 GB read + 0.94 GB written).  Bytes counted = read + written."""
+    import torch
+    import paper_2605_06055_amd as moe
+    from paper_2605_06055_amd.layer import MoeLayer
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+    dst = torch.empty_like(src)
+    ms = event_time_ms(lambda i: dst.copy_(src), 20)
+    out = {"dtod_memcpy_GBps": round(2 * n / ms / 1e6, 1)}
+    del src, dst
+    T, H = 65536, 7168
+    L = MoeLayer(T, H, 1, 1, 1, schedule=moe.MOE_SCHEDULE_PREFILL, separate_expert_out=False)
+    x = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+    kd = torch.zeros((T, 1), dtype=torch.int32, device="cuda")
+    L.dispatch(x, kd)
+    ms = event_time_ms(lambda i: moe.moe_dispatch(L.shape, x, kd, L._plan_struct, L.window), 20)
+    out["own_copy_kernel_GBps"] = round(2 * T * H * 2 / ms / 1e6, 1)
+    return out
+
+
 def cpu_baseline(cfg, budget_s=12.0):
     """The oracle as it stands, single thread, on a bounded sample of the same workload."""
     import oracle
@@ -194,6 +217,7 @@ def main():
     ap.add_argument("--workload", default="prefill", choices=sorted(DESCR))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode T=128 leg of the headline run")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the streaming-copy ceiling measurement")
     ap.add_argument("--decode-sweep", action="store_true",
                     help="also time decode layers at the paper's Table 2 points: hidden 4096 and 7168, "
                          "batch 16..144 (HIP graph replay, cold buffers); printed to stderr and added to the JSON")
@@ -249,6 +273,9 @@ def main():
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic_for(f"{dom}:{args.workload}")},
     }
+    if not args.no_ceiling:
+        out["copy_ceiling"] = copy_ceiling()
+        out["frac_of_copy_ceiling"] = round(main_res["gbs"] / max(out["copy_ceiling"].values()), 4)
     if args.workload == "prefill" and not args.no_decode:
         dcfg = wl.CONFIGS["decode"]
         d = measure(dcfg, max(args.steps, 400), args.warmup, 20, use_graph=True)

@@ -432,3 +432,34 @@ def test_decode_schedule_limits(moe):
     _case(moe, K, 1024, 128, moe.MOE_SCHEDULE_DECODE, H=64, label="decode N=8192 E=1024")
     K = wl.random_routing(rng, 64, 128, 1024)          # k = 128 with duplicates
     _case(moe, K, 1024, 1024, moe.MOE_SCHEDULE_DECODE, H=8, label="decode k=128 E=R=1024")
+
+
+def test_optional_outputs_and_side_stream(moe):
+    """send_idx / recv tables may be NULL; calls issued on a non-default stream stay on that stream."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    from paper_2605_06055_amd.binding import _PlanStruct
+    for cfg, sch in ((wl.Config("opt", T=700, H=256, k=8, E=64, R=8, seed=1), moe.MOE_SCHEDULE_PREFILL),
+                     (wl.Config("opt", T=90, H=256, k=8, E=64, R=8, seed=2), moe.MOE_SCHEDULE_DECODE)):
+        w = wl.make(cfg)
+        ref_plan, ref_window, ref_yexp, ref_y = oracle.layer(w.X, w.K, w.W, w.scale, cfg.E, cfg.R)
+        layer = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, schedule=sch)
+        p = layer.plan
+        p.workspace.fill_(0x5A)                                   # stale scratch must not matter
+        ps = _PlanStruct(p.expert_count.data_ptr(), p.rank_count.data_ptr(), p.expert_offset.data_ptr(),
+                         p.region_base.data_ptr(), None, p.row_map.data_ptr(), p.status.data_ptr(),
+                         p.workspace.data_ptr(), p.workspace.numel(), None, None, None)
+        p.send_idx.fill_(-9)
+        side = torch.cuda.Stream()
+        xd, kd, wd = to_device(w.X), to_device(w.K), to_device(w.W)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            if sch == moe.MOE_SCHEDULE_PREFILL:
+                moe.moe_plan(layer.shape, kd, ps)
+            moe.moe_dispatch(layer.shape, xd, kd, ps, layer.window)
+            layer.expert_out.copy_(to_device(ref_yexp))
+            moe.moe_combine(layer.shape, layer.expert_out, wd, ps, layer.y)
+        side.synchronize()
+        assert np.all(to_host(p.send_idx) == -9)                  # not written when NULL was passed
+        assert np.array_equal(to_host(p.row_map).reshape(cfg.T, cfg.k), ref_plan.row_map)
+        assert to_host(layer.window).tobytes() == ref_window.tobytes()
+        assert max_ulp(to_host(layer.y), ref_y) <= 1
