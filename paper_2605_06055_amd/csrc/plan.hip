@@ -3,8 +3,8 @@
 // offset s of every branch and the row map o[K] + s.  No payload is touched.
 //
 // The small offset must be the number of EARLIER branches (smaller flat index t*k+j) with the same
-// expert, so it cannot come from global atomics (arbitrary order).  It is built the way the paper
-// describes the Layout kernel -- per-block counting plus prefix accumulation over earlier blocks:
+// expert, so it cannot come from global atomics (arbitrary order).  It is built from counts per tile
+// and a prefix over the tiles in front, the scheme the paper names for its Layout kernel:
 //   pass 1  plan_tile_hist : one workgroup per tile of branches -> LDS histogram -> tile_hist[tile][E+1]
 //                            (slot E counts ids outside [0,E) other than -1)
 //   pass 2  plan_rank      : one workgroup (16 waves) per tile.  Column sums of tile_hist over earlier
