@@ -263,9 +263,11 @@ def main():
     out = {
         "metric": "dispatch+combine effective HBM GB/s", "value": round(main_res["gbs"], 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(main_res["ms_per_step"], 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": DESCR[args.workload], "schedule": main_res["schedule"],
-                   "payload_bytes_per_step": cfg.payload_bytes, "accumulate": "fp32", "buffer_sets": n_sets},
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",       # arithmetic of the path: fp32 multiply-add in combine (dispatch is a byte copy, the plan int32)
+        "data": "synthetic",
+        "config": {"workload": DESCR[args.workload], "schedule": main_res["schedule"], "storage": "bf16",
+                   "payload_bytes_per_step": cfg.payload_bytes, "buffer_sets": n_sets},
         "us_per_layer": round(main_res["us_per_layer"], 2),
         "frac_of_hbm_peak": round(main_res["gbs"] / HBM_PEAK_GBS, 4),
         "kernels": {k: round(v, 2) for k, v in kern.items()},
