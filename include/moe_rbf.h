@@ -63,7 +63,7 @@ enum moe_status {
 };
 
 #define MOE_MAX_EXPERTS 1024
-#define MOE_AUTO_DECODE_MAX_BRANCHES 2048
+#define MOE_AUTO_DECODE_MAX_BRANCHES 4096
 #define MOE_DECODE_MAX_BRANCHES 8192
 
 typedef struct moe_shape {
