@@ -53,6 +53,38 @@ class MoeLayer:
     def combine(self, topk_w, stream=None):
         B.moe_combine(self.shape, self.expert_out, topk_w, self._plan_struct, self.y, stream)
 
+    def bind(self, x, topk_idx, topk_w, stream=None):
+        """Pre-marshalled calls for a serving loop that re-runs the layer on the same buffers: returns
+        (dispatch, combine) closures whose ctypes arguments were converted once.  The stream is the one
+        current at bind time unless given.  (Per-call marshalling costs about 7 us in Python, more than
+        a decode kernel takes.)"""
+        import ctypes
+        lib = B.load_library()
+        vp = ctypes.c_void_p
+        shp, ps = ctypes.byref(self.shape), ctypes.byref(self._plan_struct)
+        st = vp(B._stream(stream))
+        xp, kp, wp = vp(B._ptr(x)), vp(B._ptr(topk_idx)), vp(B._ptr(topk_w))
+        win, eo, yp = vp(B._ptr(self.window)), vp(B._ptr(self.expert_out)), vp(B._ptr(self.y))
+        self._bound_keepalive = (x, topk_idx, topk_w)
+        prefill = self.schedule == B.MOE_SCHEDULE_PREFILL
+        plan_fn, dispatch_fn, combine_fn = lib.moe_plan, lib.moe_dispatch, lib.moe_combine
+
+        def dispatch():
+            if prefill:
+                rc = plan_fn(shp, kp, ps, st)
+                if rc:
+                    raise B.MoeError(rc, "moe_plan")
+            rc = dispatch_fn(shp, xp, kp, ps, win, st)
+            if rc:
+                raise B.MoeError(rc, "moe_dispatch")
+
+        def combine():
+            rc = combine_fn(shp, eo, wp, ps, yp, st)
+            if rc:
+                raise B.MoeError(rc, "moe_combine")
+
+        return dispatch, combine
+
     def standin_expert(self, topk_idx, scale):
         """Stand-in for the expert FFNs, outside the library: every placed row times its expert's
         scalar, rounded to storage (torch ops; not part of the measured path)."""

@@ -242,6 +242,14 @@ def test_identity_expert_round_trip_on_gpu(moe):
     layer.combine(to_device(w.W))
     torch.cuda.synchronize()
     assert max_ulp(to_host(layer.y), w.X) <= 1
+    # the pre-marshalled calls do the same thing
+    first = to_host(layer.y).copy()
+    layer.y.zero_(), layer.window.zero_()
+    dispatch, combine = layer.bind(to_device(w.X), to_device(w.K), to_device(w.W))
+    dispatch()
+    combine()
+    torch.cuda.synchronize()
+    assert to_host(layer.y).tobytes() == first.tobytes()
 
 
 def test_hip_graph_replay_matches_eager(moe):
