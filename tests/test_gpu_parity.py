@@ -471,3 +471,28 @@ def test_optional_outputs_and_side_stream(moe):
         assert np.array_equal(to_host(p.row_map).reshape(cfg.T, cfg.k), ref_plan.row_map)
         assert to_host(layer.window).tobytes() == ref_window.tobytes()
         assert max_ulp(to_host(layer.y), ref_y) <= 1
+
+
+def test_two_layers_on_two_streams_concurrently(moe):
+    """The library keeps no state between calls: two layers issued on two streams at the same time
+    (prefill schedule on one, fused decode schedule on the other) both match the oracle."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    jobs = []
+    for cfg, sch in ((wl.Config("a", T=3000, H=2048, k=8, E=256, R=32, seed=61), moe.MOE_SCHEDULE_PREFILL),
+                     (wl.Config("b", T=120, H=7168, k=8, E=256, R=32, seed=62), moe.MOE_SCHEDULE_DECODE)):
+        w = wl.make(cfg)
+        ref = oracle.layer(w.X, w.K, w.W, w.scale, cfg.E, cfg.R)
+        layer = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, schedule=sch)
+        layer.expert_out.copy_(to_device(ref[2]))
+        jobs.append((layer, to_device(w.X), to_device(w.K), to_device(w.W), ref, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for rep in range(10):
+        for layer, xd, kd, wd, ref, st in jobs:
+            with torch.cuda.stream(st):
+                layer.dispatch(xd, kd)
+                layer.combine(wd)
+    torch.cuda.synchronize()
+    for layer, xd, kd, wd, ref, st in jobs:
+        assert np.array_equal(to_host(layer.plan.row_map).reshape(ref[0].row_map.shape), ref[0].row_map)
+        assert to_host(layer.window).tobytes() == ref[1].tobytes()
+        assert max_ulp(to_host(layer.y), ref[3]) <= 1
