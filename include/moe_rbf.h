@@ -21,9 +21,10 @@
  *     synchronises: all work is enqueued on the caller's stream and results are
  *     valid once that stream reaches the end of the call's work.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *   - The shared library does not name a HIP runtime of its own: it binds to the libamdhip64 that the
- *     process has already loaded with global symbol visibility (e.g. the one PyTorch ships), so the
- *     caller's streams and device pointers belong to the same runtime as the library's launches.
+ *   - The shared library needs the HIP runtime by soname (libamdhip64.so.7) and uses whichever copy the
+ *     process has loaded first.  A process that embeds PyTorch must load torch's copy before this library
+ *     (the Python binding does), so that the caller's streams and device pointers belong to the same
+ *     runtime as the library's launches.
  *   - moe_shape and moe_plan_t are read on the host during the call only.
  *   - All tensors are row-major and dense.  X, window, expert_out and Y share
  *     `dtype`; K is int32; W is float32; all counts and offsets are int32.

@@ -40,16 +40,17 @@ def library_path() -> str:
 
 
 def _bind_hip_runtime() -> None:
-    """libmoe_rbf.so carries no DT_NEEDED on a HIP runtime: it must bind to the ONE runtime of the
-    process, so that the caller's streams and device pointers mean the same thing to it.  With
-    PyTorch that is the libamdhip64 inside the torch wheel (not /opt/rocm's); it is promoted to
-    the global symbol scope before the library is opened."""
+    """libmoe_rbf.so needs the HIP runtime by soname.  PyTorch ships its own libamdhip64 (same soname, not
+    /opt/rocm's file); if the library were opened first it would pull in /opt/rocm's copy and torch
+    would then load a second runtime whose streams and devices are not the library's.  Loading torch's
+    copy first makes the dynamic loader reuse it for the library: one runtime per process."""
     try:
         import torch
         cand = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
     except ImportError:
         cand = ""
-    ctypes.CDLL(cand if os.path.exists(cand) else "libamdhip64.so", mode=ctypes.RTLD_GLOBAL)
+    if os.path.exists(cand):
+        ctypes.CDLL(cand, mode=ctypes.RTLD_GLOBAL)
 
 
 def load_library():

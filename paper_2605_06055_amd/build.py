@@ -15,10 +15,10 @@ HIPCC_FLAGS = [
     # packed-fp32 instruction selection is switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
-    # No DT_NEEDED on a HIP runtime: the library binds to the runtime already loaded in the process
-    # (PyTorch ships its own libamdhip64), so streams and device pointers belong to ONE runtime.
-    "-no-hip-rt",
 ]
+# The library depends on the HIP runtime by soname (libamdhip64.so.7).  A process that already holds a
+# runtime with that soname (PyTorch ships its own copy) keeps using that one: the Python binding makes
+# sure torch's copy is loaded first, so streams and device pointers belong to ONE runtime.
 
 
 def build_library(out: str = LIB, defines: dict | None = None, verbose: bool = False) -> str:

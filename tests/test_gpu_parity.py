@@ -496,3 +496,15 @@ def test_two_layers_on_two_streams_concurrently(moe):
         assert np.array_equal(to_host(layer.plan.row_map).reshape(ref[0].row_map.shape), ref[0].row_map)
         assert to_host(layer.window).tobytes() == ref[1].tobytes()
         assert max_ulp(to_host(layer.y), ref[3]) <= 1
+
+
+def test_c_abi_from_a_plain_host_program(moe):
+    """tests/abi_check (built by __graft_entry__.build) drives the library from C++ with hipMalloc'd
+    buffers and its own stream, without Python or torch in the process, and checks against the oracle."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "abi_check")
+    assert os.path.exists(exe), "tests/abi_check is missing: run __graft_entry__.build()"
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    print(res.stdout, res.stderr, flush=True)
+    assert res.returncode == 0 and "abi_check: ok" in res.stdout
