@@ -31,6 +31,22 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def event_percentiles_us(fn, iters, per_call=1):
+    """p10/p50/p90 of the duration of single fn() calls (microseconds, divided by per_call), each
+    bracketed by its own pair of HIP events; the calls still run back to back."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(ev):
+        a.record()
+        fn(i)
+        b.record()
+    torch.cuda.synchronize()
+    d = sorted(a.elapsed_time(b) * 1e3 / per_call for a, b in ev)
+    pick = lambda q: round(d[min(len(d) - 1, int(q * len(d)))], 2)
+    return {"p10": pick(0.10), "p50": pick(0.50), "p90": pick(0.90), "samples": len(d)}
+
+
 def event_time_ms(fn, iters):
     """Average duration of fn() over `iters` back-to-back calls, HIP events on the launch stream."""
     import torch
@@ -137,15 +153,22 @@ def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1, 
     s = Sets(cfg, n_sets, schedule, sources, quant)
     for i in range(warmup):
         s.step(i)
+    n_pct = max(50, min(steps, 200))                  # layers whose wall time is taken one by one
     if use_graph:
         per_graph = max(n_sets, 20)
         ms, g = graph_time_ms(s.step, per_graph, max(1, steps // per_graph))
+        pct = event_percentiles_us(lambda i: g.replay(), max(10, n_pct // per_graph), per_call=per_graph)
+        pct["of"] = f"whole replays of the {per_graph}-layer graph, divided by {per_graph}"
     elif bound and not quant:
         s.bind()
         ms = event_time_ms(s.step_bound, steps)
+        pct = event_percentiles_us(s.step_bound, n_pct)
+        pct["of"] = "single layers, each between its own pair of events, launched back to back"
     else:
         ms = event_time_ms(s.step, steps)
-    res = {"ms_per_step": ms, "us_per_layer": ms * 1e3, "gbs": cfg.payload_bytes / (ms * 1e-3) / 1e9,
+        pct = event_percentiles_us(s.step, n_pct)
+        pct["of"] = "single layers, each between its own pair of events, launched back to back"
+    res = {"wall_us_per_layer": pct, "ms_per_step": ms, "us_per_layer": ms * 1e3, "gbs": cfg.payload_bytes / (ms * 1e-3) / 1e9,
            "schedule": "decode" if s.schedule == moe.MOE_SCHEDULE_DECODE else "prefill", "buffer_sets": n_sets,
            "launch": "hip graph replay" if use_graph else ("eager, pre-marshalled calls" if bound else "eager")}
     half = cfg.T * cfg.H * cfg.elem_bytes * (1 + cfg.k)           # bytes of dispatch alone == combine alone
@@ -191,25 +214,37 @@ def copy_ceiling():
     return out
 
 
-def cpu_baseline(cfg, budget_s=12.0):
-    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+def cpu_baseline(cfg, budget_s=10.0):
+    """The oracle as it stands on a bounded sample of the same workload: single thread (the headline
+    figure) and, beside it, the same source built with OpenMP so that the token loops of dispatch and
+    combine use every host core (the plan stays serial)."""
     import oracle
     import workloads as wl
     T = min(cfg.T, 2048)                           # a slice of the batch keeps the leg to seconds
     sub = cfg.with_(T=T)
     w = wl.make(sub)
-    reps, spent = 0, 0.0
-    while reps < 1 or (spent < budget_s and reps < 50):
-        t0 = time.perf_counter()
-        pl = oracle.plan(w.K, sub.E, sub.R)
-        window = oracle.dispatch(w.X, pl.row_map, pl.window_rows)
-        oracle.combine(window, w.W, pl.row_map)
-        spent += time.perf_counter() - t0
-        reps += 1
-    per = spent / reps
+
+    def timed(budget):
+        reps, spent = 0, 0.0
+        while reps < 1 or (spent < budget and reps < 50):
+            t0 = time.perf_counter()
+            pl = oracle.plan(w.K, sub.E, sub.R)
+            window = oracle.dispatch(w.X, pl.row_map, pl.window_rows)
+            oracle.combine(window, w.W, pl.row_map)
+            spent += time.perf_counter() - t0
+            reps += 1
+        return spent / reps, reps
+
+    per, reps = timed(budget_s)
+    with oracle.all_cores():
+        threads = oracle.threads()
+        per_all, reps_all = timed(budget_s / 2)
     return {"value": sub.payload_bytes / per / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"first {T} tokens of the workload (plan+dispatch+combine, identity expert), "
-                      f"{reps} repetitions, {per * 1e3:.1f} ms each", "host_cpus": os.cpu_count()}
+                      f"{reps} repetitions, {per * 1e3:.1f} ms each",
+            "all_cores": {"value": sub.payload_bytes / per_all / 1e9, "unit": "GB/s", "cores": threads,
+                          "sample": f"same sample, {reps_all} repetitions, {per_all * 1e3:.1f} ms each"},
+            "host_cpus": os.cpu_count()}
 
 
 def traffic_for(kernel):
@@ -282,6 +317,7 @@ def main():
         "config": {"workload": DESCR[args.workload], "schedule": main_res["schedule"], "storage": "bf16",
                    "payload_bytes_per_step": cfg.payload_bytes, "buffer_sets": n_sets},
         "us_per_layer": round(main_res["us_per_layer"], 2),
+        "wall_us_per_layer": main_res["wall_us_per_layer"],
         "frac_of_hbm_peak": round(main_res["gbs"] / HBM_PEAK_GBS, 4),
         "kernels": {k: round(v, 2) for k, v in kern.items()},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
@@ -295,12 +331,18 @@ def main():
         dcfg = wl.CONFIGS["decode"]
         d = measure(dcfg, max(args.steps, 400), args.warmup, 20, use_graph=True)
         de = measure(dcfg, max(args.steps, 400), args.warmup, 20, use_graph=False, bound=True)
+        dw = measure(dcfg, max(args.steps, 400), args.warmup, 1, use_graph=True)
+        log(f"[decode, graph replay, one buffer set (warm cache)] {json.dumps(dw)}")
         log(f"[decode, graph replay] {json.dumps(d)}")
         log(f"[decode, eager launches from Python, pre-marshalled] {json.dumps(de)}")
         out["decode"] = {"workload": DESCR["decode"], "us_per_layer": round(d["us_per_layer"], 2),
                          "value": round(d["gbs"], 1), "unit": "GB/s",
                          "frac_of_hbm_peak": round(d["gbs"] / HBM_PEAK_GBS, 4), "buffer_sets": d["buffer_sets"],
                          "launch": "one HIP graph of 20 layers replayed (a layer is 2 kernels of ~5 us)",
+                         "wall_us_per_layer": d["wall_us_per_layer"],
+                         "us_per_layer_warm": round(dw["us_per_layer"], 2),
+                         "warm": "the same graph on ONE buffer set (33 MB, resident in the Infinity Cache): not an "
+                                 "HBM figure, shown for contrast only",
                          "us_per_layer_eager": round(de["us_per_layer"], 2),
                          "eager_launch": "kernel by kernel from Python with pre-marshalled ctypes arguments "
                                          "(MoeLayer.bind); marshalling per call would cost ~7 us per launch",

@@ -17,8 +17,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "moe_oracle.c")
 _LIB = os.path.join(_HERE, "libmoe_oracle.so")
 
+_LIB_OMP = os.path.join(_HERE, "libmoe_oracle_omp.so")
+
 BF16, F32 = 0, 1
 _lib = None
+_serial = _parallel = None
 
 
 def build(force: bool = True) -> str:
@@ -27,18 +30,50 @@ def build(force: bool = True) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-mfma", "-ffp-contract=off", "-Wall", "-Wextra", "-shared",
                                "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    if force or not os.path.exists(_LIB_OMP) or os.path.getmtime(_LIB_OMP) < os.path.getmtime(_SRC):
+        # the same file with the token loops of dispatch and combine handed to all cores (benchmark only)
+        subprocess.check_call(["gcc", "-O2", "-mfma", "-ffp-contract=off", "-fopenmp", "-Wall", "-Wextra", "-shared",
+                               "-fPIC", "-o", _LIB_OMP, _SRC, "-lm"])
     return _LIB
 
 
+def _open(path):
+    lib = ctypes.CDLL(path)
+    for name in ("moe_ref_plan", "moe_ref_plan_multi", "moe_ref_dispatch", "moe_ref_combine", "moe_ref_combine_f64",
+                 "moe_ref_expert_standin", "moe_ref_threads"):
+        getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
 def _load():
-    global _lib
+    global _lib, _serial
     if _lib is None:
         build(force=False)
-        _lib = ctypes.CDLL(_LIB)
-        for name in ("moe_ref_plan", "moe_ref_plan_multi", "moe_ref_dispatch", "moe_ref_combine", "moe_ref_combine_f64",
-                     "moe_ref_expert_standin"):
-            getattr(_lib, name).restype = ctypes.c_int
+        _lib = _serial = _open(_LIB)
     return _lib
+
+
+def threads() -> int:
+    """Threads the loaded build hands the token loops of dispatch and combine to (1 unless all_cores())."""
+    return int(_load().moe_ref_threads())
+
+
+class all_cores:
+    """``with oracle.all_cores():`` runs dispatch and combine of the enclosed calls on every host core
+    (the OpenMP build of the same source).  For the benchmark's baseline; the tests use the serial build."""
+
+    def __enter__(self):
+        global _lib, _parallel
+        _load()
+        if _parallel is None:
+            _parallel = _open(_LIB_OMP)
+        _lib = _parallel
+        return self
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = _serial
+        return False
 
 
 def _p(a: np.ndarray):

@@ -36,6 +36,18 @@
 #include <stdint.h>
 #include <string.h>
 
+/* The token loops of dispatch and combine are independent per token (distinct rows, distinct outputs).
+ * The tests use the serial build; the benchmark's all-cores baseline compiles this same file with
+ * -fopenmp, which only hands the tokens of those two loops to several threads. */
+#ifdef _OPENMP
+#include <omp.h>
+#define TOKENS_IN_PARALLEL _Pragma("omp parallel for schedule(static)")
+int moe_ref_threads(void) { return omp_get_max_threads(); }
+#else
+#define TOKENS_IN_PARALLEL
+int moe_ref_threads(void) { return 1; }
+#endif
+
 enum { MOE_REF_BF16 = 0, MOE_REF_F32 = 1 };
 
 /* ---- storage conversions -------------------------------------------------- */
@@ -229,6 +241,7 @@ int moe_ref_dispatch(int32_t T, int32_t H, int32_t k, int32_t elem_bytes,
                      void *window)              /* [rows, H]; only mapped rows are written */
 {
   const size_t row_bytes = (size_t)H * (size_t)elem_bytes;
+  TOKENS_IN_PARALLEL
   for (int32_t t = 0; t < T; ++t) {
     for (int32_t j = 0; j < k; ++j) {
       const int32_t p = row_map[(int64_t)t * k + j];
@@ -248,6 +261,7 @@ int moe_ref_combine(int32_t T, int32_t H, int32_t k, int32_t dtype,
                     void *Y)                   /* [T, H] out */
 {
   if (dtype != MOE_REF_BF16 && dtype != MOE_REF_F32) return -2;
+  TOKENS_IN_PARALLEL
   for (int32_t t = 0; t < T; ++t) {
     for (int32_t h = 0; h < H; ++h) {
       float acc = 0.0f;

@@ -526,3 +526,22 @@ def test_pins_catch_mutant(name, tmp_path):
     res = subprocess.run([sys.executable, "-c", child], capture_output=True, text=True, timeout=300)
     assert res.returncode != 3, f"no pin notices the planted mistake '{name}'"
     assert res.returncode == 0, f"mutant '{name}' crashed the checker instead of failing a pin:\n{res.stderr[-2000:]}"
+
+
+def test_all_cores_build_gives_the_serial_results():
+    """The benchmark's all-cores baseline is the same source with the token loops of dispatch and combine
+    split over threads: it must reproduce the serial build bit for bit."""
+    cfg = wl.CONFIGS["tiny"].with_(T=300, H=256, E=16, R=4, k=4)
+    w = wl.make(cfg, seed=5)
+    pl = oracle.plan(w.K, cfg.E, cfg.R)
+    window = oracle.dispatch(w.X, pl.row_map, pl.window_rows)
+    y = oracle.combine(window, w.W, pl.row_map)
+    assert oracle.threads() == 1
+    with oracle.all_cores():
+        assert oracle.threads() >= 1
+        pl2 = oracle.plan(w.K, cfg.E, cfg.R)
+        window2 = oracle.dispatch(w.X, pl2.row_map, pl2.window_rows)
+        y2 = oracle.combine(window2, w.W, pl2.row_map)
+    assert oracle.threads() == 1
+    assert np.array_equal(pl.row_map, pl2.row_map)
+    assert np.array_equal(window, window2) and np.array_equal(y, y2)
