@@ -62,34 +62,6 @@ __global__ __launch_bounds__(BLOCK) void dispatch_slices_kernel(const u32x4 *__r
 
 constexpr int kSlotBatch = 8;     // slots of a token ranked together
 
-__device__ __forceinline__ void decode_tables_block(const int32_t *__restrict__ K, const Dims &d, const PlanView &p,
-                                                    int *lds) {
-  const int E = d.E, tid = threadIdx.x, nthreads = blockDim.x;
-  int *total = lds;            // [E]
-  int *g = total + E;          // [E+1]
-  int *others = g + E + 1;     // [E]  several source ranks only
-  int *pre = others + E;       // [E]
-  int *misc = pre + E;         // [2]
-  const bool multi = p.source_count != nullptr;
-  for (int e = tid; e < E; e += nthreads) {
-    total[e] = 0;
-    others[e] = 0;
-    pre[e] = 0;
-  }
-  if (tid == 0) misc[0] = 0;
-  __syncthreads();
-  for (int i = tid; i < d.N; i += nthreads) {
-    const int e = K[i];
-    if (e >= 0 && e < E) atomicAdd(&total[e], 1);
-    else if (e != -1) atomicAdd(&misc[0], 1);
-  }
-  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
-  __syncthreads();
-  if (tid < kWave) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
-  __syncthreads();
-  write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, misc[0], misc + 1);
-}
-
 // QUANT: the workgroup holds a whole row (chunks == 1), quantises it once and fans the codes and the
 // row's scale out instead of the bf16 payload.
 template <int BLOCK, int V, bool QUANT>
@@ -102,7 +74,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
   __shared__ int part[(BLOCK / kWave) * kSlotBatch];            // per-wave packed counts of a slot batch
   constexpr int kWaves = BLOCK / kWave;
   if ((int)blockIdx.x == d.T * chunks) {
-    decode_tables_block(K, d, p, lds);
+    tables_from_ids_block(K, d, p, lds);
     return;
   }
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;

@@ -16,7 +16,7 @@
 //                            are used for COUNTS only, which do not depend on order.  One extra workgroup
 //                            writes the count/offset tables.
 // Both kernels are latency-bound (a few microseconds): loads are requested before LDS is cleared and
-// the serial chain is kept to three barriers.
+// the serial chain is kept to three barriers.  Small batches skip pass 1 (see plan_rank_kernel<true>).
 #include "device_utils.h"
 #include "launch.h"
 #include "plan_tables.h"
@@ -69,6 +69,10 @@ __device__ __forceinline__ int row16_inclusive_scan(int v) {
 
 // Pass 2.  Workgroups 0..tiles-1 rank one tile each; workgroup `tiles` writes the count/offset tables.
 // A tile is split into 16 contiguous wave segments (64 branches each when the tile is 1024 branches).
+// FUSED: there was no pass 1.  Every workgroup counts the ids outside its own tile itself (in front of the
+// tile -> `before`, behind it -> `total`), which costs N LDS atomics per workgroup instead of a launch:
+// worth it for batches of up to about twelve thousand branches.
+template <bool FUSED>
 __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__restrict__ K,
                                                                 const int32_t *__restrict__ tile_hist, int tiles,
                                                                 int tile, Dims d, PlanView p) {
@@ -86,6 +90,10 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   const bool multi = p.source_count != nullptr;
 
   if (me == tiles) {                   // tables workgroup
+    if (FUSED) {
+      tables_from_ids_block(K, d, p, lds);
+      return;
+    }
     for (int e = tid; e <= E; e += kPlanBlock) total[e] = 0;
     for (int e = tid; e < 2 * E; e += kPlanBlock) others[e] = 0;     // others and pre
     __syncthreads();
@@ -104,12 +112,40 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   // the first round's id is requested before anything else and stays in a register
   const long long i_first = seg_start + lane;
   const int id_first = i_first < d.N ? K[i_first] : -1;
+  constexpr int kBatch = 8;            // FUSED: ids of other tiles, kBatch per thread and trip
+  const int tile_start = me * tile;    // FUSED only runs with N <= tiles * tile well inside 31 bits
+  const int tile_end = min(tile_start + tile, d.N);
+  int other[kBatch];
+  if (FUSED) {
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = u * kPlanBlock + tid;
+      other[u] = (i < d.N && (i < tile_start || i >= tile_end)) ? K[i] : -1;
+    }
+  }
 
   for (int e = tid; e <= E; e += kPlanBlock) total[e] = 0;
   for (int e = tid; e < 3 * E; e += kPlanBlock) before[e] = 0;       // before, others and pre
   for (int x = tid; x < kPlanWaves * E; x += kPlanBlock) wcur[x] = 0;
   __syncthreads();
-  sum_columns<false>(tile_hist, tiles, E + 1, me, total, before, E);
+  if (FUSED) {
+    for (int i0 = 0; i0 < d.N; i0 += kBatch * kPlanBlock) {
+      int next[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {                 // the next trip's ids are requested first
+        const int i = i0 + (kBatch + u) * kPlanBlock + tid;
+        next[u] = (i < d.N && (i < tile_start || i >= tile_end)) ? K[i] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int e = other[u];
+        if (e >= 0 && e < E) atomicAdd(i0 + u * kPlanBlock + tid < tile_start ? &before[e] : &total[e], 1);
+        other[u] = next[u];
+      }
+    }
+  } else {
+    sum_columns<false>(tile_hist, tiles, E + 1, me, total, before, E);
+  }
   if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
   // histogram of each wave's segment (counts only: atomics are order-free here)
   for (int rd = 0; rd < rounds; ++rd) {
@@ -118,7 +154,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
     if (e >= 0 && e < E) atomicAdd(&wcur[wave * E + e], 1);
   }
   __syncthreads();
-  if (wave == 0) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
+  if (!FUSED && wave == 0) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
   // exclusive prefix of the segment counts over the 16 waves, seeded with the count in earlier tiles:
   // element (e, w) sits in lane w of a 16-lane row, so one DPP row scan does it
   for (int x0 = 0; x0 < kPlanWaves * E; x0 += kPlanBlock) {
@@ -128,8 +164,14 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
     const int c = in ? wcur[w * E + e] : 0;
     const int incl = row16_inclusive_scan(c);
     if (in) wcur[w * E + e] = before[e] + incl - c;
+    // FUSED: total[e] held the ids behind the tile; the last wave's lane adds those in front and the tile's own
+    if (FUSED && in && w == kPlanWaves - 1) total[e] += before[e] + incl;
   }
   __syncthreads();
+  if (FUSED) {
+    if (wave == 0) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
+    __syncthreads();
+  }
 
   // stable ranks inside each wave segment: 64 branches per round, rounds in index order.  Lanes with
   // the same id all read the segment's running count, then the lowest of them advances it.
@@ -188,19 +230,33 @@ hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s) {
   return launch(plan_empty_kernel, dim3(1), dim3(kPlanBlock), lds, s, d, p);
 }
 
-hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, hipStream_t s) {
-  const int tile = plan_tile_size(d.N);
-  const int tiles = plan_tile_count(d.N);
-  const size_t lds1 = (size_t)(d.E + 1) * sizeof(int);
-  hipError_t err = launch(plan_tile_hist_kernel, dim3(tiles), dim3(kPlanBlock), lds1, s, K, d.N, d.E, tile, tile_hist);
-  if (err != hipSuccess) return err;
-  const size_t lds2 = (size_t)(5 * d.E + 2 + kPlanWaves * d.E + 2) * sizeof(int);
-  if (lds2 > 64 * 1024) {   // beyond the default dynamic LDS limit (E > ~800): raise it once per process
-    static const hipError_t raised = hipFuncSetAttribute((const void *)plan_rank_kernel,
+// Largest batch (in tiles of 1024 branches) planned with one launch.  Measured, E = 256, graph replay:
+// one launch / two launches = 7.6 / 8.9 us at 8192 branches, 8.6 / 9.1 at 16384 (9.3 / 9.1 with Zipf
+// routing, whose hot bins serialise the LDS atomics), 10.7 / 9.2 at 32768, 26 / 11.7 at 131072.
+#ifndef MOE_PLAN_FUSED_MAX_TILES
+#define MOE_PLAN_FUSED_MAX_TILES 12
+#endif
+
+template <bool FUSED>
+static hipError_t launch_plan_rank(const Dims &d, const int32_t *K, const PlanView &p, const int32_t *tile_hist,
+                                   int tiles, int tile, hipStream_t s) {
+  const size_t lds = (size_t)(5 * d.E + 2 + kPlanWaves * d.E + 2) * sizeof(int);
+  if (lds > 64 * 1024) {   // beyond the default dynamic LDS limit (E > ~800): raise it once per process
+    static const hipError_t raised = hipFuncSetAttribute((const void *)plan_rank_kernel<FUSED>,
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (raised != hipSuccess) return raised;
   }
-  return launch(plan_rank_kernel, dim3(tiles + 1), dim3(kPlanBlock), lds2, s, K, tile_hist, tiles, tile, d, p);
+  return launch(plan_rank_kernel<FUSED>, dim3(tiles + 1), dim3(kPlanBlock), lds, s, K, tile_hist, tiles, tile, d, p);
+}
+
+hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, hipStream_t s) {
+  const int tile = plan_tile_size(d.N);
+  const int tiles = plan_tile_count(d.N);
+  if (tiles <= MOE_PLAN_FUSED_MAX_TILES) return launch_plan_rank<true>(d, K, p, tile_hist, tiles, tile, s);
+  const size_t lds1 = (size_t)(d.E + 1) * sizeof(int);
+  hipError_t err = launch(plan_tile_hist_kernel, dim3(tiles), dim3(kPlanBlock), lds1, s, K, d.N, d.E, tile, tile_hist);
+  if (err != hipSuccess) return err;
+  return launch_plan_rank<false>(d, K, p, tile_hist, tiles, tile, s);
 }
 
 }  // namespace moe_rbf

@@ -107,4 +107,35 @@ __device__ __forceinline__ void write_plan_tables(const int *own, const int *oth
   }
 }
 
+// One workgroup builds the whole histogram from the routing ids themselves (counts only: LDS integer
+// atomics) and writes the tables.  Used where no per-tile histograms exist: the fused decode dispatch and
+// the single-launch plan.  LDS: 4E + 3 ints.  Must be called by every thread of the workgroup.
+__device__ __forceinline__ void tables_from_ids_block(const int32_t *__restrict__ K, const Dims &d, const PlanView &p,
+                                                    int *lds) {
+  const int E = d.E, tid = threadIdx.x, nthreads = blockDim.x;
+  int *total = lds;            // [E]
+  int *g = total + E;          // [E+1]
+  int *others = g + E + 1;     // [E]  several source ranks only
+  int *pre = others + E;       // [E]
+  int *misc = pre + E;         // [2]
+  const bool multi = p.source_count != nullptr;
+  for (int e = tid; e < E; e += nthreads) {
+    total[e] = 0;
+    others[e] = 0;
+    pre[e] = 0;
+  }
+  if (tid == 0) misc[0] = 0;
+  __syncthreads();
+  for (int i = tid; i < d.N; i += nthreads) {
+    const int e = K[i];
+    if (e >= 0 && e < E) atomicAdd(&total[e], 1);
+    else if (e != -1) atomicAdd(&misc[0], 1);
+  }
+  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
+  __syncthreads();
+  if (tid < kWave) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
+  __syncthreads();
+  write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, misc[0], misc + 1);
+}
+
 }  // namespace moe_rbf

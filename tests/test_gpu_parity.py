@@ -353,6 +353,23 @@ def test_multi_source_notify(moe, schedule):
     assert np.array_equal(ref.expert_offset, oracle.plan(wl.make(cfg, seed=9).K, 32, 4).expert_offset)
 
 
+def test_plan_on_both_sides_of_the_single_launch_limit(moe):
+    """The explicit plan runs as one launch up to 12 tiles of 1024 branches and as two launches above:
+    the same cases (masked and invalid ids, fixed stride, several source ranks, skewed routing) on both sides."""
+    rng = np.random.default_rng(77)
+    for T in (1535, 1536, 1537, 2500):                # N = 12280, 12288 (last single launch), 12296, 20000
+        cfg = wl.CONFIGS["skewed"].with_(T=T, H=64, E=64, R=8)
+        w = wl.make(cfg, seed=T)
+        K = w.K.copy()
+        K[rng.integers(0, T, 40), rng.integers(0, cfg.k, 40)] = -1
+        K[rng.integers(0, T, 9), rng.integers(0, cfg.k, 9)] = cfg.E + 3
+        run_case(moe, w.X, K, w.W, w.scale, cfg.E, cfg.R, moe.MOE_SCHEDULE_PREFILL, label=f"limit T={T}")
+        run_case(moe, w.X, K, w.W, w.scale, cfg.E, cfg.R, moe.MOE_SCHEDULE_PREFILL, stride=T * cfg.k // cfg.R,
+                 label=f"limit T={T} fixed stride")
+        M = rng.integers(0, 300, size=(cfg.R, cfg.E)).astype(np.int32)
+        run_multi(moe, cfg, M, cfg.R // 2, moe.MOE_SCHEDULE_PREFILL, seed=T)
+
+
 # --------------------------------------------------------------------------- row-wise quantised dispatch
 
 def run_quant(moe, cfg, schedule, stride=0, seed=0, scale_rows=None):
