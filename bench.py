@@ -269,6 +269,9 @@ def main():
     ap.add_argument("--decode-sweep", action="store_true",
                     help="also time decode layers at the paper's Table 2 points: hidden 4096 and 7168, "
                          "batch 16..144 (HIP graph replay, cold buffers); printed to stderr and added to the JSON")
+    ap.add_argument("--prefill-sweep", action="store_true",
+                    help="also time prefill layers (explicit plan) at 1024..16384 tokens of the H=7168 layer, the "
+                         "token axis of the paper's prefill figure, with the bf16 and the quantised dispatch")
     ap.add_argument("--quant", action="store_true",
                     help="also time prefill T=4096 and decode T=128 with the row-wise quantised dispatch "
                          "(FP8 E4M3 codes + fp32 row scales on the dispatch side, bf16 combine)")
@@ -392,6 +395,20 @@ def main():
                 log(f"[decode sweep] {json.dumps(row)}")
                 sweep.append(row)
         out["decode_sweep"] = sweep
+    if args.prefill_sweep:
+        sweep = []
+        for T in (1024, 2048, 4096, 8192, 16384):
+            c = wl.CONFIGS["prefill"].with_(name=f"prefill_T{T}", T=T)
+            n_sets = 4 if c.payload_bytes < 400e6 else 1          # keep the working set well over 256 MB
+            r = measure(c, 100, 5, n_sets, schedule=1)
+            q = measure(c, 100, 5, n_sets, schedule=1, quant=True)
+            row = {"T": T, "us_per_layer": round(r["us_per_layer"], 1), "GBps": round(r["gbs"], 1),
+                   "plan_us": round(r["kernels"]["plan_us"], 1), "dispatch_us": round(r["kernels"]["dispatch_us"], 1),
+                   "combine_us": round(r["kernels"]["combine_us"], 1),
+                   "quant_dispatch_us": round(q["kernels"]["dispatch_us"], 1)}
+            log(f"[prefill sweep] {json.dumps(row)}")
+            sweep.append(row)
+        out["prefill_sweep"] = sweep
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
         out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
