@@ -242,7 +242,7 @@ def cpu_baseline(cfg, budget_s=10.0):
     return {"value": sub.payload_bytes / per / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"first {T} tokens of the workload (plan+dispatch+combine, identity expert), "
                       f"{reps} repetitions, {per * 1e3:.1f} ms each",
-            "all_cores": {"value": sub.payload_bytes / per_all / 1e9, "unit": "GB/s", "cores": threads,
+            "all_cores": {"value": round(sub.payload_bytes / per_all / 1e9, 3), "unit": "GB/s", "cores": threads,
                           "sample": f"same sample, {reps_all} repetitions, {per_all * 1e3:.1f} ms each"},
             "host_cpus": os.cpu_count()}
 
