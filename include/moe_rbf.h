@@ -121,7 +121,8 @@ int moe_window_rows(const moe_shape *shape, int64_t *out_rows);
 /* Which schedule moe_dispatch will use for this shape (resolves AUTO). */
 int moe_resolve_schedule(const moe_shape *shape, int32_t *out_schedule);
 
-/* Prefill Layout + Notify (paper, Section 5.2; Algorithm 1 steps "Layout" and "Notify", single source rank).
+/* Prefill Layout + Notify (paper, Section 5.2; Algorithm 1 steps "Layout" and "Notify"; one source rank, or
+ * one of several when plan->source_count carries the gathered count matrix).
  *   topk_idx : device, int32 [T*k], read only.
  *   Writes every array of `plan` (send_idx only if non-NULL) and zero-initialises status itself.
  *   Moves no payload.  Results do not depend on the launch configuration. */
