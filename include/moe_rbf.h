@@ -143,6 +143,9 @@ int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx,
  * names no format; this library's format is OCP FP8 E4M3 codes plus one float32 scale per row:
  *   amax = max |x| over the token row, scale = amax / 448, code = e4m3(x * (448 / amax)) rounded to nearest
  *   even; an all-zero row has scale 1.  Every destination row of a token receives the same codes and scale.
+ *   Non-finite inputs: a NaN element does not enter amax and yields a NaN code (S.1111.111, sign unspecified);
+ *   a row with an infinite element has scale +Inf, signed-zero codes for its finite elements and NaN codes
+ *   for the infinite ones.
  *   shape->dtype must be MOE_DTYPE_BF16 (type of x) and H <= 32768; schedules and plan as for moe_dispatch.
  *   window_q     : device, [moe_window_rows, H] bytes; only rows some branch maps to are written.
  *   window_scale : device, float32 [moe_window_rows]; same rows. */

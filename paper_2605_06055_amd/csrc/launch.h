@@ -31,7 +31,7 @@ struct Dims {
   int64_t stride;   // region_stride_rows (0 = tight)
 };
 
-// Branches per plan tile for N routed branches (multiple of 256) and the tile count.
+// Branches per plan tile for N routed branches (1024, doubled until at most 512 tiles remain) and the tile count.
 int plan_tile_size(int64_t N);
 int plan_tile_count(int64_t N);
 

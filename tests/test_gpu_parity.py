@@ -372,13 +372,16 @@ def test_plan_on_both_sides_of_the_single_launch_limit(moe):
 
 # --------------------------------------------------------------------------- row-wise quantised dispatch
 
-def run_quant(moe, cfg, schedule, stride=0, seed=0, scale_rows=None):
+def run_quant(moe, cfg, schedule, stride=0, seed=0, scale_rows=None, plant=None):
     from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
     w = wl.make(cfg, seed=seed)
     X = w.X.copy()
     if scale_rows is not None:                       # per-row magnitudes spread over many binades
         f = wl.bf16_bits_to_f32(X) * scale_rows[:, None]
         X = wl.f32_to_bf16_bits(f.astype(np.float32))
+    if plant is not None:                            # (row, column, bf16 bits) triples: Inf / NaN elements
+        for (r, c, bits) in plant:
+            X[r, c] = bits
     T, H, k, E, R = cfg.T, cfg.H, cfg.k, cfg.E, cfg.R
     ref = oracle.plan(w.K, E, R, stride)
     layer = MoeLayer(T, H, k, E, R, schedule=schedule, region_stride_rows=stride)
@@ -398,8 +401,11 @@ def run_quant(moe, cfg, schedule, stride=0, seed=0, scale_rows=None):
     ref_q, ref_s = oracle.dispatch_quant(X, ref.row_map, max(rows, 1), fill=0xAA)
     got_q, got_s = wq.cpu().numpy(), ws.cpu().numpy()
     assert got_s.tobytes() == ref_s.tobytes(), "row scales"
-    bad = np.count_nonzero(got_q != ref_q)
+    # a NaN code is S.1111.111 with either sign: which sign a NaN product carries is not part of the format
+    both_nan = ((got_q & 0x7F) == 0x7F) & ((ref_q & 0x7F) == 0x7F)
+    bad = np.count_nonzero((got_q != ref_q) & ~both_nan)
     assert bad == 0, f"{bad} of {got_q.size} fp8 codes differ"
+    return got_q, got_s
 
 
 @pytest.mark.parametrize("schedule", ["prefill", "decode"])
@@ -415,6 +421,12 @@ def test_quantised_dispatch(moe, schedule):
     zero[::5] = 0.0                                   # all-zero rows: scale 1, codes 0
     run_quant(moe, cfg, sch, seed=3, scale_rows=zero)
     run_quant(moe, cfg, sch, stride=70, seed=4)       # fixed stride with overflow
+    # non-finite inputs: a NaN element gives a NaN code and does not enter amax; a row with an infinite
+    # element has scale +Inf, zero codes (signed) for its finite elements and NaN codes for the infinite ones
+    PINF, NINF, NAN, NNAN = 0x7F80, 0xFF80, 0x7FC0, 0xFFC1
+    q, sc = run_quant(moe, cfg, sch, seed=5, plant=[(0, 3, NAN), (0, 100, NNAN), (1, 7, PINF), (2, 9, NINF),
+                                                    (2, 10, NAN), (3, 0, PINF), (3, 511, NINF)])
+    assert np.isinf(sc).sum() >= 1 and not np.isnan(sc).any()
 
 
 def test_quantised_dispatch_full_prefill(moe):
