@@ -4,6 +4,8 @@ Bar: counts, offsets, small offsets, row map and every dispatched window byte bi
 combine within 1 bf16 ulp (fp32 storage: bit-exact up to the same bound in fp32 ulps), with the
 fp32 accumulate / ascending-j / fused-multiply-add decision taken in the same precision on both sides.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -437,10 +439,11 @@ def test_quantised_dispatch_full_prefill(moe):
 
 def test_seeded_random_shapes(moe):
     """Forty seeded shapes over both schedules: odd sizes, masked / invalid / duplicate ids, fixed strides,
-    several source ranks, fp32 and bf16 storage, routing degrees up to 100 and E up to the limit."""
-    rng = np.random.default_rng(2024)
+    several source ranks, fp32 and bf16 storage, routing degrees up to 100 and E up to the limit.
+    MOE_FUZZ_CASES / MOE_FUZZ_SEED in the environment run a longer or a different series."""
+    rng = np.random.default_rng(int(os.environ.get("MOE_FUZZ_SEED", "2024")))
     from paper_2605_06055_amd.layer import to_device
-    for case in range(40):
+    for case in range(int(os.environ.get("MOE_FUZZ_CASES", "40"))):
         R = int(rng.choice([1, 2, 3, 4, 8, 16, 32]))
         Er = int(rng.choice([1, 2, 3, 8, 32]))
         E = min(R * Er, 1024)
