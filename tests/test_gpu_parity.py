@@ -465,6 +465,26 @@ def test_seeded_random_shapes(moe):
         _case(moe, K, E, R, sch, H=H, stride=stride, dtype=dtype, seed=case, label=f"fuzz {case}")
 
 
+def test_plan_left_by_decode_dispatch_is_reusable(moe):
+    """A later call on identical routing may skip planning: the explicit schedule's dispatch, given the plan
+    state a fused decode dispatch left behind, places new payload in the same rows."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    from paper_2605_06055_amd import binding as B
+    cfg = wl.CONFIGS["decode"]
+    w = wl.make(cfg)
+    ref = oracle.plan(w.K, cfg.E, cfg.R)
+    layer = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, schedule=moe.MOE_SCHEDULE_DECODE)
+    kd = to_device(w.K)
+    layer.dispatch(to_device(w.X), kd)                               # plans and places X
+    X2 = wl.make(cfg, seed=99).X                                     # new payload, same routing
+    reuse = B.MoeShape(T=cfg.T, H=cfg.H, k=cfg.k, E=cfg.E, R=cfg.R, dtype=moe.MOE_DTYPE_BF16,
+                       schedule=moe.MOE_SCHEDULE_PREFILL, rank_id=0, region_stride_rows=0)
+    moe.moe_dispatch(reuse, to_device(X2), None, layer.plan, layer.window)      # no moe_plan, no ids
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(layer.plan.row_map).reshape(cfg.T, cfg.k), ref.row_map)
+    assert to_host(layer.window).tobytes() == oracle.dispatch(X2, ref.row_map, ref.window_rows).tobytes()
+
+
 def test_decode_schedule_limits(moe):
     """Largest batch the fused decode kernel accepts (8192 branches) with the largest expert count."""
     rng = np.random.default_rng(77)
