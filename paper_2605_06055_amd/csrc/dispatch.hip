@@ -263,13 +263,24 @@ hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void
   }
 }
 
-hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K, const PlanView &p, void *window,
-                                  hipStream_t s) {
-  constexpr int B = MOE_DECODE_BLOCK, V = MOE_DECODE_VEC;
+template <int V>
+static hipError_t launch_decode_dispatch_v(const Dims &d, const void *x, const int32_t *K, const PlanView &p,
+                                           void *window, hipStream_t s) {
+  constexpr int B = MOE_DECODE_BLOCK;
   const int chunks = (d.H16 + B * V - 1) / (B * V);
   const size_t lds = (size_t)(4 * d.E + 1 + 2) * sizeof(int);
   return launch(decode_dispatch_kernel<B, V, false>, dim3((unsigned)d.T * (unsigned)chunks + 1u), dim3(B), lds, s,
                 (const u32x4 *)x, K, window, (float *)nullptr, d, p, chunks);
+}
+
+hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K, const PlanView &p, void *window,
+                                  hipStream_t s) {
+  // Every workgroup of a token repeats the token's counting, whose cost grows with the batch: from about
+  // 900 branches on, two vectors per lane (half as many workgroups per token) win; below that, more
+  // workgroups spread the stores over more compute units.  Measured at H = 7168, k = 8 (one / two vectors):
+  // T = 16: 3.8 / 4.1 us, T = 80: 4.8 / 5.1 us, T = 128: 5.7 / 5.5 us, T = 144: 6.4 / 6.0 us.
+  if (d.H16 > MOE_DECODE_BLOCK && d.N >= 896) return launch_decode_dispatch_v<2>(d, x, K, p, window, s);
+  return launch_decode_dispatch_v<MOE_DECODE_VEC>(d, x, K, p, window, s);
 }
 
 // Whole-row workgroup shapes for the quantised kernels: (threads, vectors per thread) covering H16 <= 4096.
