@@ -151,12 +151,18 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
         x = i < d.N ? K[i] : -1;
       }
       const int ahead = first + j0 - i;               // slot u is behind id i  <=>  u + ahead > 0
+      // ids outside [0,E) never satisfy either test: as unsigned values they are huge (or x > e)
+      if (fixed) {
 #pragma unroll
-      for (int u = 0; u < kSlotBatch; ++u) {
-        // ids outside [0,E) never satisfy either test: x - lo wraps to a huge unsigned value or x > e
-        below[u] += __popcll(__ballot((unsigned)(x - lo[u]) < (unsigned)(e[u] - lo[u])));
-        front[u] += __popcll(__ballot(x == e[u] && ahead + u > 0));
+        for (int u = 0; u < kSlotBatch; ++u)
+          below[u] += __popcll(__ballot((unsigned)(x - lo[u]) < (unsigned)(e[u] - lo[u])));
+      } else {
+#pragma unroll
+        for (int u = 0; u < kSlotBatch; ++u) below[u] += __popcll(__ballot((unsigned)x < (unsigned)e[u]));
       }
+#pragma unroll
+      for (int u = 0; u < kSlotBatch; ++u)
+        front[u] += __popcll(__ballot(x == e[u]) & __ballot(ahead + u > 0));   // two masks, and-ed as scalars
     }
     if (j0 > 0) __syncthreads();                      // the previous batch's exchange has been read
     {
