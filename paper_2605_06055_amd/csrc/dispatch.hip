@@ -21,27 +21,33 @@ namespace moe_rbf {
 
 constexpr int kSlices = 8;   // column slices per row = XCDs per device
 
-// Prefill dispatch.  Work unit = (J consecutive branches of one token, column slice c of 8).
-// Workgroup b handles slice c = b % 8.  Workgroups are handed to the 8 XCDs round-robin, so XCD c only
+// Prefill dispatch.  Work unit = (J consecutive branches of one token, column slice c of 8); a workgroup
+// holds U units.  Workgroup b handles slice c = b % 8.  Workgroups are handed to the 8 XCDs round-robin, so XCD c only
 // ever touches column slice c: the k re-reads of X[t]'s slice by the branches of a token hit in that
 // XCD's L2 (X is fetched from HBM once), every wave issues few 16-byte stores per lane, and the 8 XCDs
 // together lay down whole destination rows.  Stores are streaming (nontemporal) so that they do not
 // evict the X slices from L2; loads are ordinary so that they stay.
 // (If the hardware maps workgroups differently the result is unchanged; only the L2 reuse is lost.)
-template <int BLOCK, int J>
+template <int BLOCK, int J, int U>
 __global__ __launch_bounds__(BLOCK) void dispatch_slices_kernel(const u32x4 *__restrict__ X,
                                                                 const int32_t *__restrict__ row_map,
-                                                                u32x4 *__restrict__ window, int k, int H16, int slice) {
-  const int g = blockIdx.x / kSlices;
-  const int c = blockIdx.x - g * kSlices;
+                                                                u32x4 *__restrict__ window, int k, int H16, int slice,
+                                                                int N) {
+  // U units per workgroup, each with BLOCK / U lanes: narrow slices (small H) still fill the workgroup
+  constexpr int kLanes = BLOCK / U;
+  const int unit = U == 1 ? 0 : (int)threadIdx.x / kLanes;
+  const int lane = U == 1 ? (int)threadIdx.x : (int)threadIdx.x % kLanes;
+  const int g = (blockIdx.x / kSlices) * U + unit;
+  const int c = blockIdx.x % kSlices;
   const int n = g * J;                       // J consecutive branches of one token (J divides k)
+  if (U > 1 && n >= N) return;
   int row[J];
 #pragma unroll
-  for (int u = 0; u < J; ++u) row[u] = uniform(row_map[n + u]);
+  for (int u = 0; u < J; ++u) row[u] = kLanes % kWave == 0 ? uniform(row_map[n + u]) : row_map[n + u];
   const int t = n / k;
   const int end = min((c + 1) * slice, H16);
   const u32x4 *src = X + (size_t)t * (size_t)H16;
-  for (int col = c * slice + threadIdx.x; col < end; col += BLOCK) {
+  for (int col = c * slice + lane; col < end; col += kLanes) {
     const u32x4 v = src[col];
 #pragma unroll
     for (int u = 0; u < J; ++u)
@@ -249,24 +255,48 @@ __global__ __launch_bounds__(BLOCK) void dispatch_quant_rows_kernel(const u32x4 
   }
 }
 
+template <int J, int U>
+static hipError_t launch_dispatch_ju(const Dims &d, const void *x, const PlanView &p, void *window, int slice,
+                                     hipStream_t s) {
+  const unsigned units = (unsigned)(d.N / J);
+  const dim3 grid((units + U - 1) / U * (unsigned)kSlices);
+  return launch(dispatch_slices_kernel<128, J, U>, grid, dim3(128), 0, s, (const u32x4 *)x,
+                (const int32_t *)p.row_map, (u32x4 *)window, d.k, d.H16, slice, d.N);
+}
+
 hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void *window, hipStream_t s) {
-  // several branches of a token per workgroup when a slice is short, so that the number of workgroups
-  // stays within what the dispatcher sustains
+  // A workgroup should move a few KB, so that the grid stays within what the dispatcher sustains (about 3000
+  // workgroups per microsecond), with its lanes busy.
+  //   Normally one unit per workgroup; a unit takes J branches of its token until it moves 4 KB (1.75 KB
+  //   when the slice fills both waves): one load feeds J stores.
+  //   Slices of at most 16 columns (H <= 1024 for bf16), or of at most 32 when the routing degree does not
+  //   allow enough branches per unit: a unit is as many lanes as the slice has columns (a power of two, at
+  //   least 8) and 128 / lanes units, i.e. branches of neighbouring tokens, share the workgroup; J until it
+  //   moves 8 KB.
+  // Measured in a plan -> dispatch -> combine sequence, k = 8, us per dispatch, this rule / one unit only:
+  //   H = 512, T = 131072: 212 / 544;  H = 1024, T = 131072: 466 / 828;  H = 2048, T = 65536: 436 / 459;
+  //   H = 2048, k = 6, T = 8192: 37 / 58 (launches alone).
   const int slice = (d.H16 + kSlices - 1) / kSlices;
   const int slice_bytes = slice * 16;
-  const int want = slice <= 64 ? 4096 : 1792;
-  int J = 1;
+  int lanes = 8;                                   // lanes of a unit
+  while (lanes < 128 && lanes < slice) lanes *= 2;
+  int want = slice <= 64 ? 4096 : 1792;
+  int U = 1, J = 1;
   while (J < 8 && J * slice_bytes < want && d.k % (2 * J) == 0) J *= 2;
-  const dim3 grid((unsigned)(d.N / J) * (unsigned)kSlices);
-  const u32x4 *xs = (const u32x4 *)x;
-  u32x4 *win = (u32x4 *)window;
-  const int32_t *rm = p.row_map;
-  switch (J) {
-    case 1: return launch(dispatch_slices_kernel<128, 1>, grid, dim3(128), 0, s, xs, rm, win, d.k, d.H16, slice);
-    case 2: return launch(dispatch_slices_kernel<128, 2>, grid, dim3(128), 0, s, xs, rm, win, d.k, d.H16, slice);
-    case 4: return launch(dispatch_slices_kernel<128, 4>, grid, dim3(128), 0, s, xs, rm, win, d.k, d.H16, slice);
-    default: return launch(dispatch_slices_kernel<128, 8>, grid, dim3(128), 0, s, xs, rm, win, d.k, d.H16, slice);
+  if (slice <= 16 || (slice <= 32 && J * slice_bytes < want)) {     // narrow, or the routing degree allows too few branches
+    U = 128 / lanes;
+    want = 8192;
+    J = 1;
+    while (J < 8 && U * J * slice_bytes < want && d.k % (2 * J) == 0) J *= 2;
   }
+#define GO(J_, U_) if (J == J_ && U == U_) return launch_dispatch_ju<J_, U_>(d, x, p, window, slice, s)
+  GO(1, 1); GO(2, 1); GO(4, 1); GO(8, 1);
+  GO(1, 2); GO(2, 2); GO(4, 2); GO(8, 2);
+  GO(1, 4); GO(2, 4); GO(4, 4); GO(8, 4);
+  GO(1, 8); GO(2, 8); GO(4, 8); GO(8, 8);
+  GO(1, 16); GO(2, 16); GO(4, 16); GO(8, 16);
+#undef GO
+  return hipErrorInvalidValue;
 }
 
 template <int V>
