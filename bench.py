@@ -27,6 +27,10 @@ DESCR = {
 }
 
 
+def rounded(kern):
+    return {k: (round(v, 2) if isinstance(v, float) else v) for k, v in kern.items()}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -194,6 +198,24 @@ def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1, 
     else:
         kern["dispatch_us"] = event_time_ms(s.dispatch_only, steps) * 1e3
         kern["combine_us"] = event_time_ms(s.combine_only, steps) * 1e3
+        # The same calls inside plan -> dispatch -> combine sequences, each between its own events: a kernel
+        # then runs in the cache state the sequence leaves it (a loop of dispatches alone finds X in the
+        # Infinity Cache whenever it fits), at the price of an event-to-event gap of a few microseconds
+        # that these figures include.
+        import torch
+        calls = ([s.plan_only] if "plan_us" in kern else []) + [s.dispatch_only, s.combine_only]
+        names = (["plan_us"] if "plan_us" in kern else []) + ["dispatch_us", "combine_us"]
+        n = max(20, min(steps, 200))
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(n)]
+        torch.cuda.synchronize()
+        for i, e in enumerate(ev):
+            e[0].record()
+            for c, call in enumerate(calls):
+                call(i)
+                e[c + 1].record()
+        torch.cuda.synchronize()
+        res["kernels_in_sequence"] = {name: round(sum(e[c].elapsed_time(e[c + 1]) for e in ev) / n * 1e3, 2)
+                                      for c, name in enumerate(names)}
     kern["dispatch_gbs"] = half / kern["dispatch_us"] / 1e3
     kern["combine_gbs"] = half / kern["combine_us"] / 1e3
     res["kernels"] = kern
@@ -332,7 +354,8 @@ def main():
         "us_per_layer": round(main_res["us_per_layer"], 2),
         "wall_us_per_layer": main_res["wall_us_per_layer"],
         "frac_of_hbm_peak": round(main_res["gbs"] / HBM_PEAK_GBS, 4),
-        "kernels": {k: round(v, 2) for k, v in kern.items()},
+        "kernels": rounded(kern),
+        "kernels_in_sequence": main_res.get("kernels_in_sequence"),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": traffic_for(f"{dom}:{args.workload}")},
@@ -367,7 +390,7 @@ def main():
                                          "(MoeLayer.bind); marshalling per call would cost ~7 us per launch",
                          "cache": "cold: 20 disjoint buffer sets (660 MB) rotated so no step finds its lines in "
                                   "the 256 MB Infinity Cache",
-                         "kernels": {k: round(v, 2) for k, v in d["kernels"].items()}}
+                         "kernels": rounded(d["kernels"])}
     if args.quant:
         pc, dc = wl.CONFIGS["prefill"], wl.CONFIGS["decode"]
         qp = measure(pc, args.steps, args.warmup, 1, quant=True)
@@ -395,9 +418,9 @@ def main():
         log(f"[decode as one of {S} sources, graph replay] {json.dumps(md)}")
         out["multi_source"] = {"sources": S,
                                "prefill_us_per_layer": round(mp["us_per_layer"], 2),
-                               "prefill_kernels": {k: round(v, 2) for k, v in mp["kernels"].items()},
+                               "prefill_kernels": rounded(mp["kernels"]),
                                "decode_us_per_layer": round(md["us_per_layer"], 2),
-                               "decode_kernels": {k: round(v, 2) for k, v in md["kernels"].items()}}
+                               "decode_kernels": rounded(md["kernels"])}
     if args.decode_sweep:
         sweep = []
         for H in (4096, 7168):
