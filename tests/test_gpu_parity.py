@@ -485,6 +485,23 @@ def test_plan_left_by_decode_dispatch_is_reusable(moe):
     assert to_host(layer.window).tobytes() == oracle.dispatch(X2, ref.row_map, ref.window_rows).tobytes()
 
 
+@pytest.mark.parametrize("T,H,k", [(112, 4104, 8), (128, 8200, 8), (300, 8192, 3), (1024, 16392, 8), (100, 4104, 9)])
+def test_decode_dispatch_wide_rows(moe, T, H, k):
+    """Rows wider than one workgroup pass (more than 512 16-byte columns) on both sides of the batch size at
+    which the fused dispatch switches to two vectors per lane (896 branches), with ragged row tails, masked
+    and invalid ids, a fixed stride and several source ranks."""
+    rng = np.random.default_rng(T + H)
+    E, R = 64, 8
+    K = wl.random_routing(rng, T, k, E, distinct=True, p_masked=0.05, p_invalid=0.02)
+    a = _case(moe, K, E, R, moe.MOE_SCHEDULE_DECODE, H=H, seed=T, label=f"wide rows T={T} H={H}")
+    b = _case(moe, K, E, R, moe.MOE_SCHEDULE_PREFILL, H=H, seed=T, label=f"wide rows T={T} H={H} (explicit)")
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+    _case(moe, K, E, R, moe.MOE_SCHEDULE_DECODE, H=H, stride=max(1, T * k // R), seed=T, label="wide rows, fixed stride")
+    cfg = wl.Config("widerows", T=T, H=H, k=k, E=E, R=R, seed=T)
+    run_multi(moe, cfg, rng.integers(0, 50, size=(R, E)).astype(np.int32), R // 2, moe.MOE_SCHEDULE_DECODE, seed=T)
+
+
 def test_decode_schedule_limits(moe):
     """Largest batch the fused decode kernel accepts (8192 branches) with the largest expert count."""
     rng = np.random.default_rng(77)
