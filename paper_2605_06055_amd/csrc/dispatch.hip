@@ -7,6 +7,7 @@
 //   token from the routing ids themselves (see the decode section below).
 #include "device_utils.h"
 #include "launch.h"
+#include "moe_rbf.h"
 #include "plan_tables.h"
 #include "quant.h"
 
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
                                                                 int chunks) {
   extern __shared__ int lds[];                                  // tables workgroup; several-sources prefix tables
   __shared__ int part[(BLOCK / kWave) * kSlotBatch];            // per-wave packed counts of a slot batch
+  __shared__ int part_m[(BLOCK / kWave) * kSlotBatch];          // per-wave rows of the other source ranks
   constexpr int kWaves = BLOCK / kWave;
   if ((int)blockIdx.x == d.T * chunks) {
     tables_from_ids_block(K, d, p, lds);
@@ -114,19 +116,43 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
     scale = quantise_row<BLOCK, V>(v, has, q, red);
   }
 
-  // several source ranks: rows of the other sources in front of a slot's sub-block =
-  // (their rows in the experts below e, inside the region for fixed stride) + (rows of lower ranks for e)
+  // Several source ranks: rows of the other sources in front of a slot's sub-block =
+  // (their rows in the experts below e, inside the region for fixed stride) + (rows of lower ranks for e),
+  // i.e. sums over parts of the count matrix M.  A thread owns a few columns of M and keeps, per column, the
+  // sum over the other ranks and the sum over the lower ranks; a slot's two terms are then masked sums of
+  // these over the workgroup (wave reduction + the LDS exchange the id counts use anyway).
   const bool multi = p.source_count != nullptr;
-  int *oth_scan = lds;             // [E+1] exclusive scan over e of the other sources' counts
-  int *others = oth_scan + d.E + 1;   // [E]
-  int *pre = others + d.E;         // [E]
+  constexpr int kCols = (MOE_MAX_EXPERTS + BLOCK - 1) / BLOCK;     // columns a thread may own
+  int col_all[kCols], col_pre[kCols], col_id[kCols];
+#pragma unroll
+  for (int q2 = 0; q2 < kCols; ++q2) col_all[q2] = col_pre[q2] = 0, col_id[q2] = -1;
   if (multi) {
-    for (int e = tid; e < 2 * d.E; e += BLOCK) others[e] = 0;
-    __syncthreads();
-    sum_columns<true>(p.source_count, d.R, d.E, d.me, others, pre, d.E);
-    __syncthreads();
-    if (tid < kWave) wave_exclusive_scan_lds(others, oth_scan, d.E);
-    __syncthreads();
+    const int parts = max(1, BLOCK / d.E);          // threads per column when the matrix is narrow
+    const int part = parts > 1 ? tid / d.E : 0;
+#pragma unroll
+    for (int q2 = 0; q2 < kCols; ++q2) {
+      const int col = parts > 1 ? tid - part * d.E : tid + q2 * BLOCK;
+      const bool live = parts > 1 ? (q2 == 0 && part < parts) : col < d.E;
+      if (!live) continue;
+      col_id[q2] = col;
+      const int32_t *m = p.source_count + col;
+      int all = 0, pre = 0;
+      for (int r0 = part; r0 < d.R; r0 += parts * 8) {
+        int mv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int r = r0 + u * parts;
+          mv[u] = (r < d.R && r != d.me) ? m[(size_t)r * d.E] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          all += mv[u];
+          if (r0 + u * parts < d.me) pre += mv[u];
+        }
+      }
+      col_all[q2] = all;
+      col_pre[q2] = pre;
+    }
   }
 
   const bool fixed = d.stride > 0;
@@ -170,23 +196,44 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
       for (int u = 0; u < kSlotBatch; ++u)
         front[u] += __popcll(__ballot(x == e[u]) & __ballot(ahead + u > 0));   // two masks, and-ed as scalars
     }
+    int mine_m = 0;                                   // lane u: this wave's rows of other sources in front of slot u
+    if (multi) {
+#pragma unroll
+      for (int u = 0; u < kSlotBatch; ++u) {
+        int cu = 0;
+#pragma unroll
+        for (int q2 = 0; q2 < kCols; ++q2) {
+          cu += (unsigned)(col_id[q2] - lo[u]) < (unsigned)(e[u] - lo[u]) ? col_all[q2] : 0;
+          cu += col_id[q2] == e[u] ? col_pre[q2] : 0;
+        }
+        const int tot = __builtin_amdgcn_readlane(wave_inclusive_scan(cu), kWave - 1);
+        mine_m = lane == u ? tot : mine_m;
+      }
+    }
     if (j0 > 0) __syncthreads();                      // the previous batch's exchange has been read
     {
       int mine = 0;                                   // lane u carries this wave's packed counts of slot u
 #pragma unroll
       for (int u = 0; u < kSlotBatch; ++u) mine = lane == u ? below[u] + (front[u] << 16) : mine;
-      if (lane < kSlotBatch) part[wave * kSlotBatch + lane] = mine;
+      if (lane < kSlotBatch) {
+        part[wave * kSlotBatch + lane] = mine;
+        if (multi) part_m[wave * kSlotBatch + lane] = mine_m;
+      }
     }
     __syncthreads();
-    int packed = 0;
-    if (lane < kSlotBatch)
+    int packed = 0, ahead_m = 0;
+    if (lane < kSlotBatch) {
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) packed += part[w * kSlotBatch + lane];
+      if (multi)
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) ahead_m += part_m[w * kSlotBatch + lane];
+    }
     int s = -1, row = -1;
     if (own && my_valid) {
       s = packed >> 16;
       row = (fixed ? (int)(my_rank * d.stride) : 0) + (packed & 0xffff) + s;
-      if (multi) row += oth_scan[my_e] - oth_scan[my_lo] + pre[my_e];
+      row += ahead_m;
       if (fixed && row >= (int)((my_rank + 1) * d.stride)) row = -1;
     }
     if (own && c == 0 && wave == 0) {
