@@ -74,6 +74,7 @@ class Sets:
         import workloads as wl
         import paper_2605_06055_amd as moe
         from paper_2605_06055_amd.layer import MoeLayer, to_device
+        from workloads.standin import standin_expert
         self.cfg, self.n, self.moe = cfg, n, moe
         self.layers, self.x, self.k, self.w = [], [], [], []
         self.quant, self.wq, self.ws = quant, [], []
@@ -81,18 +82,17 @@ class Sets:
             w = wl.make(cfg, seed=cfg.seed + i)
             extra = {}
             if sources > 1:
-                # the other source ranks route like this one: their counts are draws of the same workload
+                # the other source ranks route like this one: their counts are draws of the same routing law
                 # (this rank is source rank R/2; rows of the other sources are never touched here)
-                M = np.stack([np.bincount(wl.make(cfg, seed=1000 + r).K.reshape(-1), minlength=cfg.E)
-                              if r < sources else np.zeros(cfg.E, np.int64) for r in range(cfg.R)]).astype(np.int32)
+                M = wl.source_count_matrix(cfg, sources)
                 me = min(cfg.R // 2, sources - 1)
                 own = np.bincount(w.K.reshape(-1), minlength=cfg.E)
-                rows = int(M.sum() - M[me].sum() + own.sum())
+                rows = int(M.astype(np.int64).sum() - M[me].sum() + own.sum())
                 extra = dict(source_count=to_device(M), rank_id=me, window_rows=rows)
             layer = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, dtype=cfg.dtype, schedule=schedule, **extra)
             xd, kd, wd = to_device(w.X), to_device(w.K), to_device(w.W)
             layer.dispatch(xd, kd)
-            layer.standin_expert(kd, to_device(w.scale))
+            standin_expert(layer, to_device(w.scale))
             self.layers.append(layer), self.x.append(xd), self.k.append(kd), self.w.append(wd)
             if quant:     # e4m3 codes and row scales replace the bf16 window on the dispatch side
                 self.wq.append(torch.empty((layer.rows, cfg.H), dtype=torch.uint8, device="cuda"))

@@ -58,14 +58,18 @@ enum moe_status {
   MOE_ERR_SHAPE = -2,      /* T<0, H<1, k<1, E<1, R<1, E%R!=0, E>MOE_MAX_EXPERTS, rank_id outside [0,R), negative
                               stride, unknown dtype/schedule, or DECODE forced with T*k > MOE_DECODE_MAX_BRANCHES */
   MOE_ERR_ALIGN = -3,      /* H*elem_bytes not a multiple of 16, or a device pointer not 16-byte aligned */
-  MOE_ERR_OVERFLOW = -4,   /* T*k or the window row count does not fit in int32 */
-  MOE_ERR_WORKSPACE = -5,  /* plan->workspace missing or smaller than moe_workspace_bytes */
-  MOE_ERR_LAUNCH = -6      /* the HIP runtime refused a kernel launch */
+  MOE_ERR_OVERFLOW = -4,   /* T*k or the window row count does not fit in int32, or a launch grid would not:
+                              8*T*k and T*ceil(H*elem_bytes/1024) must also stay below 2^31 */
+  MOE_ERR_WORKSPACE = -5,  /* plan->workspace missing or smaller than moe_workspace_bytes (only when moe_plan
+                              uses it: batches of more than MOE_PLAN_SINGLE_LAUNCH_MAX_BRANCHES branches) */
+  MOE_ERR_LAUNCH = -6,     /* the HIP runtime refused a kernel launch */
+  MOE_ERR_OVERLAP = -7     /* x overlaps the window, or y overlaps expert_out (byte ranges known on the host) */
 };
 
 #define MOE_MAX_EXPERTS 1024
 #define MOE_AUTO_DECODE_MAX_BRANCHES 4096
 #define MOE_DECODE_MAX_BRANCHES 8192
+#define MOE_PLAN_SINGLE_LAUNCH_MAX_BRANCHES 12288 /* up to here moe_plan is one launch and ignores plan->workspace */
 
 typedef struct moe_shape {
   int32_t T;                  /* tokens (0 is legal: counts are zeroed, nothing else happens) */
@@ -95,9 +99,13 @@ typedef struct moe_plan_t {
                                     with smaller flat index t*k+j and the same expert (sendTokenIdx / expandIdx);
                                     -1 for skipped ids.  May be NULL: then it is not written. */
   int32_t *row_map;       /* [T*k]  window row of the branch = expert_offset[K] + send_idx; -1 = not placed */
-  int32_t *status;        /* [2]    {number of ids outside [0,E) other than -1, number of branches dropped for
-                                    region capacity}.  Id -1 marks an unused slot and is not an error. */
-  void *workspace;        /* device scratch for moe_plan, >= moe_workspace_bytes(shape); unused by DECODE dispatch */
+  int32_t *status;        /* [3]    {number of ids outside [0,E) other than -1, number of branches dropped for
+                                    region capacity, 1 if the rows of all source ranks together reach 2^31}.
+                                    Id -1 marks an unused slot and is not an error.  When status[2] is set (possible
+                                    only with source_count) no branch is placed: row_map is -1 everywhere, status[1] is
+                                    0 and the offset tables are unspecified; counts and send_idx are valid. */
+  void *workspace;        /* device scratch for moe_plan, >= moe_workspace_bytes(shape); unused by DECODE dispatch and
+                             by moe_plan for T*k <= MOE_PLAN_SINGLE_LAUNCH_MAX_BRANCHES (may then be NULL) */
   size_t workspace_bytes;
   /* Several source ranks (paper, Section 5.2 "Prefill Notify": gathered count matrix M, recvData).  Optional. */
   const int32_t *source_count; /* [R*E] in: M[r*E+e] = branches source rank r sends to expert e.  Row shape->rank_id is
@@ -105,8 +113,8 @@ typedef struct moe_plan_t {
                                     only source.  An expert's block then holds one sub-block per source rank, in rank
                                     order, and expert_offset[e] = o_{e,rank_id} = start of THIS rank's sub-block;
                                     expert_offset[E] = one past the last block.  The caller, who holds M, sizes tight
-                                    windows to the sum of all counts (moe_window_rows cannot know it); rows must stay
-                                    below 2^31. */
+                                    windows to the sum of all counts (moe_window_rows cannot know it).  Counts are
+                                    non-negative; a row total of 2^31 or more is reported in status[2]. */
   int32_t *recv_count;    /* [E]    out, may be NULL: rows of expert e's whole block over all sources (n^exp,
                                     recvTokenNumPerExpert); the rows a rank region receives (n^recv) are its segment sum */
   int32_t *recv_offset;   /* [E+1]  out, may be NULL: first row of expert e's whole block; [E] = one past the last block */
@@ -134,13 +142,14 @@ int moe_plan(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, 
  *   topk_idx : device, int32 [T*k]; read by the DECODE schedule only (may be NULL for PREFILL).
  *   plan     : PREFILL reads row_map; DECODE writes all of the plan exactly as moe_plan would.
  *   window   : device, [moe_window_rows, H]; only rows some branch maps to are written.
- *   x and window must not overlap. */
+ *   x and window must not overlap: MOE_ERR_OVERLAP if the T*H elements of x share a byte with the window rows
+ *   the host knows of (moe_window_rows; with plan->source_count and tight windows, the first T*k rows). */
 int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx, moe_plan_t *plan,
                  void *window, void *stream);
 
-/* Row-wise quantised dispatch (paper, Section 5.2, end of "Prefill Dispatch": with row-wise quantisation the
- * scale values go to a parallel scale tensor in the same row order; the "quant" rows of Table 2).  The paper
- * names no format; this library's format is OCP FP8 E4M3 codes plus one float32 scale per row:
+/* Row-wise quantised dispatch (paper, Section 5.2, end of "Prefill Dispatch"; the "quant" rows of Table 2):
+ * every token row is quantised once and its scale is kept in a separate float array indexed by window row.
+ * The paper names no format; this library's format is OCP FP8 E4M3 codes plus one float32 scale per row:
  *   amax = max |x| over the token row, scale = amax / 448, code = e4m3(x * (448 / amax)) rounded to nearest
  *   even; an all-zero row has scale 1.  Every destination row of a token receives the same codes and scale.
  *   Non-finite inputs: a NaN element does not enter amax and yields a NaN code (S.1111.111, sign unspecified);
@@ -158,7 +167,8 @@ int moe_dispatch_quant(const moe_shape *shape, const void *x, const int32_t *top
  *   round-to-nearest-even to shape->dtype; unplaced branches (row_map = -1) are skipped.
  *   expert_out : device, window layout, read only (may be the window buffer itself).
  *   topk_w     : device, float32 [T*k].
- *   y          : device, [T,H], every row written; must not overlap expert_out. */
+ *   y          : device, [T,H], every row written; must not overlap expert_out (MOE_ERR_OVERLAP, same extent
+ *                rule as for moe_dispatch). */
 int moe_combine(const moe_shape *shape, const void *expert_out, const float *topk_w, const moe_plan_t *plan,
                 void *y, void *stream);
 

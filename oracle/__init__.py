@@ -97,7 +97,7 @@ class Plan:
     region_base: np.ndarray    # [R+1]
     s: np.ndarray              # [T,k] small offset
     row_map: np.ndarray        # [T,k] o[K] + s, -1 when skipped
-    status: np.ndarray         # [2]   {#invalid ids, #dropped for capacity}
+    status: np.ndarray         # [3]   {#invalid ids, #dropped for capacity, rows of all sources >= 2^31}
 
     @property
     def window_rows(self) -> int:
@@ -109,7 +109,7 @@ def plan(K: np.ndarray, E: int, R: int, region_stride_rows: int = 0) -> Plan:
     T, k = K.shape
     out = Plan(np.zeros(E, np.int32), np.zeros(R, np.int32), np.zeros(E + 1, np.int32),
                np.zeros(R + 1, np.int32), np.zeros((T, k), np.int32), np.zeros((T, k), np.int32),
-               np.zeros(2, np.int32))
+               np.zeros(3, np.int32))
     rc = _load().moe_ref_plan(ctypes.c_int32(T), ctypes.c_int32(k), ctypes.c_int32(E), ctypes.c_int32(R),
                               ctypes.c_int64(region_stride_rows), _p(K), _p(out.c_exp), _p(out.c_rank),
                               _p(out.expert_offset), _p(out.region_base), _p(out.s), _p(out.row_map),
@@ -138,7 +138,7 @@ def plan_multi(K: np.ndarray, M: np.ndarray, me: int, E: int, R: int, region_str
     T, k = K.shape
     out = MultiPlan(np.zeros(E, np.int32), np.zeros(R, np.int32), np.zeros(E + 1, np.int32),
                     np.zeros(R + 1, np.int32), np.zeros((T, k), np.int32), np.zeros((T, k), np.int32),
-                    np.zeros(2, np.int32), np.zeros((E, R), np.int32), np.zeros(E, np.int32),
+                    np.zeros(3, np.int32), np.zeros((E, R), np.int32), np.zeros(E, np.int32),
                     np.zeros(E + 1, np.int32))
     rc = _load().moe_ref_plan_multi(ctypes.c_int32(T), ctypes.c_int32(k), ctypes.c_int32(E), ctypes.c_int32(R),
                                     ctypes.c_int64(region_stride_rows), ctypes.c_int32(me), _p(K), _p(M),

@@ -112,6 +112,7 @@ int moe_ref_plan(int32_t T, int32_t k, int32_t E, int32_t R, int64_t region_stri
   const int32_t Er = E / R;
   status[0] = 0;
   status[1] = 0;
+  status[2] = 0;   /* only several sources can outgrow int32 rows: T*k itself is int32 */
   for (int32_t e = 0; e < E; ++e) c_exp[e] = 0;
 
   /* Layout: running per-expert counter == number of earlier branches with the same expert */
@@ -173,6 +174,9 @@ int moe_ref_plan(int32_t T, int32_t k, int32_t E, int32_t R, int64_t region_stri
  *   recv_offset[e] = first row of expert e's whole block; [E] = end of the last block.
  * expert_offset[e] = o_{e,me}; row_map = o_{e,me} + s.  With a fixed region stride, region d starts at
  * d*stride and a branch whose row falls at or past (d+1)*stride is dropped and counted in status[1].
+ * Rows are int32.  If the blocks of all sources together hold 2^31 rows or more, the layout cannot be
+ * expressed: status = {invalid ids, 0, 1}, no branch is placed (row_map = -1 everywhere) and the offset
+ * tables are zeroed (their content is unspecified for callers); counts and s are still those of Layout.
  */
 int moe_ref_plan_multi(int32_t T, int32_t k, int32_t E, int32_t R, int64_t region_stride_rows, int32_t me,
                        const int32_t *K, const int32_t *M /* [R*E], row `me` ignored */,
@@ -197,6 +201,19 @@ int moe_ref_plan_multi(int32_t T, int32_t k, int32_t E, int32_t R, int64_t regio
     int32_t acc = 0;
     for (int32_t e = r * Er; e < (r + 1) * Er; ++e) acc += c_exp[e];
     c_rank[r] = acc;
+  }
+  status[2] = 0;
+  int64_t all_rows = 0;
+  for (int32_t e = 0; e < E; ++e)
+    for (int32_t r = 0; r < R; ++r) all_rows += r == me ? c_exp[e] : M[(int64_t)r * E + e];
+  if (all_rows >= 2147483648LL) {
+    status[2] = 1;
+    for (int64_t i = 0; i < (int64_t)T * k; ++i) row_map[i] = -1;
+    for (int32_t e = 0; e <= E; ++e) expert_offset[e] = recv_offset[e] = 0;
+    for (int32_t e = 0; e < E; ++e) recv_count[e] = 0;
+    for (int64_t x = 0; x < (int64_t)E * R; ++x) o_all[x] = 0;
+    for (int32_t d = 0; d <= R; ++d) region_base[d] = 0;
+    return 0;
   }
   /* Notify: one running row counter over (destination rank, expert, source rank) */
   int32_t run = 0;
@@ -334,8 +351,8 @@ int moe_ref_expert_standin(int32_t T, int32_t H, int32_t k, int32_t dtype, const
 
 /* ---- Row-wise quantised dispatch (Section 5.2, last sentences of "Prefill Dispatch") -------------------
  *
- * The paper only says that, with row-wise quantisation, each row's scale goes to a parallel scale tensor
- * in the same row order; it gives no format.  Format chosen here (parity with the authors: unpinned):
+ * The paper fixes only where the scales live: one per quantised row, in an array of their own that is
+ * indexed like the window rows.  It gives no format.  Format chosen here (parity with the authors: unpinned):
  *   payload  OCP FP8 E4M3 (1-4-3 bits, bias 7, largest finite 448, no infinities, NaN = S.1111.111);
  *   amax   = max_h |x_h| over the row (as fp32);   scale = amax / 448   (stored, fp32, one rounding);
  *   inv    = 448 / amax (fp32, one rounding);      q_h = e4m3(x_h * inv), nearest-even, saturating at 448;

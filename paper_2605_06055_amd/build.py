@@ -21,9 +21,10 @@ HIPCC_FLAGS = [
 # sure torch's copy is loaded first, so streams and device pointers belong to ONE runtime.
 
 
-def build_library(out: str = LIB, defines: dict | None = None, verbose: bool = False) -> str:
+def build_library(out: str = LIB, defines: dict | None = None, verbose: bool = False,
+                  extra_flags: list | None = None) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    cmd = [hipcc, *HIPCC_FLAGS, *(extra_flags or []), "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     for k, v in (defines or {}).items():
         cmd.append(f"-D{k}={v}")
     cmd += ["-o", out] + [os.path.join(CSRC, s) for s in SOURCES]

@@ -92,6 +92,42 @@ int launch_status(hipError_t e) {
   return e == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH;
 }
 
+// Do the byte ranges [a, a+na) and [b, b+nb) share a byte?
+inline bool ranges_overlap(const void *a, uint64_t na, const void *b, uint64_t nb) {
+  const uint64_t pa = (uint64_t)reinterpret_cast<uintptr_t>(a), pb = (uint64_t)reinterpret_cast<uintptr_t>(b);
+  return na > 0 && nb > 0 && pa < pb + nb && pb < pa + na;
+}
+
+// Bytes of X / Y and (a lower bound of) the bytes of the window / expert_out buffer.  With several source
+// ranks and tight windows the row count is device data (the sum of M); the T*k rows of this rank are
+// then the part the host can be sure of.
+inline uint64_t token_bytes(const Dims &d) { return (uint64_t)d.T * (uint64_t)d.H16 * 16u; }
+inline uint64_t window_bytes(const Dims &d) {
+  const uint64_t rows = d.stride > 0 ? (uint64_t)d.R * (uint64_t)d.stride : (uint64_t)d.N;
+  return rows * (uint64_t)d.H16 * 16u;
+}
+
+int plan_call(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream) {
+  Dims d;
+  PlanView v;
+  int rc = check_shape(shape, &d);
+  if (rc != MOE_OK) return rc;
+  if (!plan) return MOE_ERR_NULL;
+  if (d.T > 0 && !topk_idx) return MOE_ERR_NULL;
+  rc = check_plan(plan, true, &v);
+  if (rc != MOE_OK) return rc;
+  if (!aligned16(topk_idx)) return MOE_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  if (d.T == 0) return launch_status(launch_plan_empty(d, v, s));
+  int32_t *tile_hist = nullptr;
+  if (plan_uses_workspace(d.N)) {
+    if (!plan->workspace || plan->workspace_bytes < workspace_need(shape)) return MOE_ERR_WORKSPACE;
+    if (!aligned16(plan->workspace)) return MOE_ERR_ALIGN;
+    tile_hist = (int32_t *)plan->workspace;
+  }
+  return launch_status(launch_plan(d, topk_idx, v, tile_hist, s));
+}
+
 }  // namespace
 
 extern "C" {
@@ -122,22 +158,7 @@ int moe_resolve_schedule(const moe_shape *shape, int32_t *out_schedule) {
 }
 
 int moe_plan(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream) {
-  Dims d;
-  PlanView v;
-  int rc = check_shape(shape, &d);
-  if (rc != MOE_OK) return rc;
-  if (!plan) return MOE_ERR_NULL;
-  if (d.T > 0 && !topk_idx) return MOE_ERR_NULL;
-  rc = check_plan(plan, true, &v);
-  if (rc != MOE_OK) return rc;
-  if (!aligned16(topk_idx)) return MOE_ERR_ALIGN;
-  hipStream_t s = (hipStream_t)stream;
-  if (d.T == 0) {
-    return launch_status(launch_plan_empty(d, v, s));
-  }
-  if (!plan->workspace || plan->workspace_bytes < workspace_need(shape)) return MOE_ERR_WORKSPACE;
-  if (!aligned16(plan->workspace)) return MOE_ERR_ALIGN;
-  return launch_status(launch_plan(d, topk_idx, v, (int32_t *)plan->workspace, s));
+  return plan_call(shape, topk_idx, plan, stream);
 }
 
 int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx, moe_plan_t *plan, void *window,
@@ -152,6 +173,7 @@ int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx,
   rc = check_plan(plan, decode, &v);
   if (rc != MOE_OK) return rc;
   if (!aligned16(x) || !aligned16(window) || (decode && !aligned16(topk_idx))) return MOE_ERR_ALIGN;
+  if (ranges_overlap(x, token_bytes(d), window, window_bytes(d))) return MOE_ERR_OVERLAP;
   hipStream_t s = (hipStream_t)stream;
   if (d.T == 0) {
     return decode ? launch_status(launch_plan_empty(d, v, s)) : MOE_OK;
@@ -174,6 +196,13 @@ int moe_dispatch_quant(const moe_shape *shape, const void *x, const int32_t *top
   if (rc != MOE_OK) return rc;
   if (!aligned16(x) || !aligned16(window_q) || !aligned16(window_scale) || (decode && !aligned16(topk_idx)))
     return MOE_ERR_ALIGN;
+  {
+    const uint64_t rows = window_bytes(d) / ((uint64_t)d.H16 * 16u);
+    if (ranges_overlap(x, token_bytes(d), window_q, rows * (uint64_t)d.H) ||
+        ranges_overlap(x, token_bytes(d), window_scale, rows * sizeof(float)) ||
+        ranges_overlap(window_q, rows * (uint64_t)d.H, window_scale, rows * sizeof(float)))
+      return MOE_ERR_OVERLAP;
+  }
   hipStream_t s = (hipStream_t)stream;
   if (d.T == 0) return decode ? launch_status(launch_plan_empty(d, v, s)) : MOE_OK;
   return launch_status(decode ? launch_decode_dispatch_quant(d, x, topk_idx, v, window_q, window_scale, s)
@@ -191,6 +220,7 @@ int moe_combine(const moe_shape *shape, const void *expert_out, const float *top
   rc = check_plan(plan, false, &v);
   if (rc != MOE_OK) return rc;
   if (!aligned16(expert_out) || !aligned16(topk_w) || !aligned16(y)) return MOE_ERR_ALIGN;
+  if (ranges_overlap(y, token_bytes(d), expert_out, window_bytes(d))) return MOE_ERR_OVERLAP;
   if (d.T == 0) return MOE_OK;
   return launch_status(launch_combine(d, expert_out, topk_w, v, y, (hipStream_t)stream));
 }
@@ -206,6 +236,7 @@ const char *moe_strerror(int status) {
     case MOE_ERR_OVERFLOW: return "branch or window row count exceeds int32";
     case MOE_ERR_WORKSPACE: return "plan workspace missing or too small";
     case MOE_ERR_LAUNCH: return "kernel launch failed";
+    case MOE_ERR_OVERLAP: return "input and output buffers overlap";
     default: return "unknown status";
   }
 }

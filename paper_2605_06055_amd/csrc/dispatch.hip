@@ -80,6 +80,8 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
   extern __shared__ int lds[];                                  // tables workgroup; several-sources prefix tables
   __shared__ int part[(BLOCK / kWave) * kSlotBatch];            // per-wave packed counts of a slot batch
   __shared__ int part_m[(BLOCK / kWave) * kSlotBatch];          // per-wave rows of the other source ranks
+  __shared__ int part_v[BLOCK / kWave];                         // per-wave number of ids inside [0,E)
+  __shared__ unsigned long long others_rows;                    // rows of the other source ranks, 64-bit
   constexpr int kWaves = BLOCK / kWave;
   if ((int)blockIdx.x == d.T * chunks) {
     tables_from_ids_block(K, d, p, lds);
@@ -127,6 +129,9 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
 #pragma unroll
   for (int q2 = 0; q2 < kCols; ++q2) col_all[q2] = col_pre[q2] = 0, col_id[q2] = -1;
   if (multi) {
+    if (tid == 0) others_rows = 0;
+    __syncthreads();
+    unsigned long long wide = 0;
     const int parts = max(1, BLOCK / d.E);          // threads per column when the matrix is narrow
     const int part = parts > 1 ? tid / d.E : 0;
 #pragma unroll
@@ -147,13 +152,16 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           all += mv[u];
+          wide += (unsigned)mv[u];
           if (r0 + u * parts < d.me) pre += mv[u];
         }
       }
       col_all[q2] = all;
       col_pre[q2] = pre;
     }
+    if (wide) atomicAdd(&others_rows, wide);        // complete once the slot exchange's barrier has passed
   }
+  bool overflow = false;                            // rows of all sources together do not fit in int32
 
   const bool fixed = d.stride > 0;
   for (int j0 = 0; j0 < d.k; j0 += kSlotBatch) {
@@ -172,6 +180,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
       front[u] = 0;
     }
     // wave-wide counts by ballot: they land in scalar registers, no lane reduction is needed
+    int n_valid = 0;
     for (int i0 = 0, pass = 0; i0 < d.N; i0 += BLOCK, ++pass) {
       const int i = i0 + tid;
       int x;
@@ -183,6 +192,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
         x = i < d.N ? K[i] : -1;
       }
       const int ahead = first + j0 - i;               // slot u is behind id i  <=>  u + ahead > 0
+      if (multi && j0 == 0) n_valid += __popcll(__ballot((unsigned)x < (unsigned)d.E));
       // ids outside [0,E) never satisfy either test: as unsigned values they are huge (or x > e)
       if (fixed) {
 #pragma unroll
@@ -219,8 +229,15 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
         part[wave * kSlotBatch + lane] = mine;
         if (multi) part_m[wave * kSlotBatch + lane] = mine_m;
       }
+      if (multi && j0 == 0 && lane == 0) part_v[wave] = n_valid;
     }
     __syncthreads();
+    if (multi && j0 == 0) {
+      unsigned own_rows = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) own_rows += (unsigned)part_v[w];
+      overflow = others_rows + own_rows >= (1ull << 31);
+    }
     int packed = 0, ahead_m = 0;
     if (lane < kSlotBatch) {
 #pragma unroll
@@ -234,7 +251,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
       s = packed >> 16;
       row = (fixed ? (int)(my_rank * d.stride) : 0) + (packed & 0xffff) + s;
       row += ahead_m;
-      if (fixed && row >= (int)((my_rank + 1) * d.stride)) row = -1;
+      if ((fixed && row >= (int)((my_rank + 1) * d.stride)) || overflow) row = -1;
     }
     if (own && c == 0 && wave == 0) {
       if (p.send_idx) p.send_idx[first + j0 + lane] = s;

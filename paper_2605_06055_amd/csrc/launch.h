@@ -34,6 +34,9 @@ struct Dims {
 // Branches per plan tile for N routed branches (1024, doubled until at most 512 tiles remain) and the tile count.
 int plan_tile_size(int64_t N);
 int plan_tile_count(int64_t N);
+// Does launch_plan read and write its tile_hist scratch for N branches?  (Small batches are planned by one
+// launch that counts every id itself and may be given tile_hist == nullptr.)
+bool plan_uses_workspace(int64_t N);
 
 hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s);
 hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, hipStream_t s);

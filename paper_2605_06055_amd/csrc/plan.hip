@@ -85,9 +85,11 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   int *pre = others + E;               // [E]    branches of the source ranks below this one
   int *wcur = pre + E;                 // [waves][E] segment histograms, then running s per wave segment
   int *misc = wcur + kPlanWaves * E;   // [2]    scratch
+  __shared__ unsigned long long others_rows;   // rows of the other source ranks, 64-bit
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int me = blockIdx.x;
   const bool multi = p.source_count != nullptr;
+  if (tid == 0) others_rows = 0;
 
   if (me == tiles) {                   // tables workgroup
     if (FUSED) {
@@ -98,11 +100,12 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
     for (int e = tid; e < 2 * E; e += kPlanBlock) others[e] = 0;     // others and pre
     __syncthreads();
     sum_columns<false>(tile_hist, tiles, E + 1, 0, total, nullptr, 0);
-    if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
+    if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E, &others_rows);
     __syncthreads();
     if (wave == 0) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
     __syncthreads();
-    write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, total[E], misc);
+    write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, total[E], misc,
+                      multi && rows_overflow(others_rows, g[E]));
     return;
   }
 
@@ -146,7 +149,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   } else {
     sum_columns<false>(tile_hist, tiles, E + 1, me, total, before, E);
   }
-  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
+  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E, &others_rows);
   // histogram of each wave's segment (counts only: atomics are order-free here)
   for (int rd = 0; rd < rounds; ++rd) {
     const long long i = seg_start + (long long)rd * kWave + lane;
@@ -173,6 +176,8 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
     __syncthreads();
   }
 
+  // rows are int32: if the blocks of all sources together do not fit, nothing is placed
+  const bool overflow = multi && rows_overflow(others_rows, g[E]);
   // stable ranks inside each wave segment: 64 branches per round, rounds in index order.  Lanes with
   // the same id all read the segment's running count, then the lowest of them advances it.
   const int bits = id_bits(E);
@@ -190,7 +195,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
       if (rank == 0 && rounds > 1) mine[e] = base + __popcll(peers);   // LDS ops of a wave execute in order
       s = base + rank;
       row = expert_first_row(g, e, d) + pre[e] + s;                    // o_{e,me} + s
-      if (row >= region_row_limit(e, d)) row = -1;
+      if (row >= region_row_limit(e, d) || overflow) row = -1;
     }
     if (in) {
       if (p.send_idx) p.send_idx[i] = s;
@@ -211,18 +216,21 @@ __global__ __launch_bounds__(kPlanBlock) void plan_empty_kernel(Dims d, PlanView
   int *others = g + E + 1;             // [E]
   int *pre = others + E;               // [E]
   int *misc = pre + E;                 // [2]
+  __shared__ unsigned long long others_rows;
   const bool multi = p.source_count != nullptr;
   for (int e = threadIdx.x; e < E; e += kPlanBlock) {
     total[e] = 0;
     others[e] = 0;
     pre[e] = 0;
   }
+  if (threadIdx.x == 0) others_rows = 0;
   __syncthreads();
-  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
+  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E, &others_rows);
   __syncthreads();
   if (threadIdx.x < kWave) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
   __syncthreads();
-  write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, 0, misc);
+  write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, 0, misc,
+                    multi && rows_overflow(others_rows, g[E]));
 }
 
 hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s) {
@@ -236,6 +244,8 @@ hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s) {
 #ifndef MOE_PLAN_FUSED_MAX_TILES
 #define MOE_PLAN_FUSED_MAX_TILES 12
 #endif
+
+bool plan_uses_workspace(int64_t N) { return plan_tile_count(N) > MOE_PLAN_FUSED_MAX_TILES; }
 
 template <bool FUSED>
 static hipError_t launch_plan_rank(const Dims &d, const int32_t *K, const PlanView &p, const int32_t *tile_hist,
@@ -252,7 +262,7 @@ static hipError_t launch_plan_rank(const Dims &d, const int32_t *K, const PlanVi
 hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, hipStream_t s) {
   const int tile = plan_tile_size(d.N);
   const int tiles = plan_tile_count(d.N);
-  if (tiles <= MOE_PLAN_FUSED_MAX_TILES) return launch_plan_rank<true>(d, K, p, tile_hist, tiles, tile, s);
+  if (!plan_uses_workspace(d.N)) return launch_plan_rank<true>(d, K, p, nullptr, tiles, tile, s);
   const size_t lds1 = (size_t)(d.E + 1) * sizeof(int);
   hipError_t err = launch(plan_tile_hist_kernel, dim3(tiles), dim3(kPlanBlock), lds1, s, K, d.N, d.E, tile, tile_hist);
   if (err != hipSuccess) return err;

@@ -10,6 +10,9 @@
 //   g         = exclusive scan over e of own + others
 // the block of expert e starts at  B[e] = region_start(d) + g[e] - g[d*E_r]  and this rank's sub-block at
 // o_{e,me} = B[e] + pre[e].  With one source rank others = pre = 0.
+//
+// Row numbers are int32.  With several sources the row total is device data (the sum of M); it is also
+// accumulated in 64 bits, and when it reaches 2^31 no branch is placed and status[2] reports it.
 #pragma once
 #include "device_utils.h"
 #include "launch.h"
@@ -34,15 +37,18 @@ __device__ __forceinline__ int region_row_limit(int e, const Dims &d) {
 // are split over `parts` groups of threads that take every parts-th row; partial sums meet in LDS with
 // integer atomics (counts: order-free).  all_sum[col] += sum over rows (without row `me` if SKIP_ME);
 // before_sum[col] += sum over rows < me (if before_sum is given; only columns < before_cols).
+// grand (optional, LDS, zeroed by the caller) += the sum of everything counted in all_sum, in 64 bits.
 // The targets must hold their starting values before the call; the caller synchronises afterwards.
 template <bool SKIP_ME>
 __device__ __forceinline__ void sum_columns(const int32_t *__restrict__ src, int rows, int cols, int me,
-                                            int *all_sum, int *before_sum, int before_cols) {
+                                            int *all_sum, int *before_sum, int before_cols,
+                                            unsigned long long *grand = nullptr) {
   const int nthreads = blockDim.x;
   const int parts = max(1, nthreads / cols);
   const int tid = threadIdx.x;
   if (parts > 1 && tid >= parts * cols) return;
   const int part = parts == 1 ? 0 : tid / cols;
+  unsigned long long wide = 0;
   for (int col = parts == 1 ? tid : tid - part * cols; col < cols; col += nthreads) {
     int all = 0, bef = 0;
     const int32_t *p = src + col;
@@ -56,22 +62,33 @@ __device__ __forceinline__ void sum_columns(const int32_t *__restrict__ src, int
 #pragma unroll
       for (int u = 0; u < 16; ++u) {
         all += v[u];
+        wide += (unsigned)v[u];
         if (r0 + u * parts < me) bef += v[u];
       }
     }
     if (all) atomicAdd(&all_sum[col], all);
     if (before_sum && bef && col < before_cols) atomicAdd(&before_sum[col], bef);
   }
+  if (grand && wide) atomicAdd(grand, wide);
+}
+
+// Do the rows of all sources together reach 2^31?  others_rows: 64-bit sum of the other sources' counts;
+// all_rows_low: the int32 sum (possibly wrapped) of own + others; this rank's own count is below 2^31, so
+// it is the difference of the two low words.
+__device__ __forceinline__ bool rows_overflow(unsigned long long others_rows, int all_rows_low) {
+  const unsigned own = (unsigned)all_rows_low - (unsigned)others_rows;
+  return others_rows + own >= (1ull << 31);
 }
 
 // One workgroup writes expert_count, rank_count, expert_offset, region_base, recv_count, recv_offset and
 // status from LDS copies of own[0..E) (count bits selected by `mask`), others/pre (nullptr with a single
 // source rank) and g[0..E].  Must be called by every thread of the workgroup.
 // Branches dropped for capacity: this rank's sub-block of expert e covers rows [o, o + own); the part at
-// or past the region's end is dropped.
+// or past the region's end is dropped.  overflow: the row total does not fit in int32 (the offset tables
+// are then meaningless and status[2] says so).
 __device__ __forceinline__ void write_plan_tables(const int *own, const int *others, const int *pre, const int *g,
                                                   const Dims &d, const PlanView &p, int n_invalid, int *lds_counter,
-                                                  int mask = -1) {
+                                                  bool overflow = false, int mask = -1) {
   const int nthreads = blockDim.x;
   const bool fixed = d.stride > 0;
   if (threadIdx.x == 0) *lds_counter = 0;
@@ -103,7 +120,8 @@ __device__ __forceinline__ void write_plan_tables(const int *own, const int *oth
   __syncthreads();
   if (threadIdx.x == 0) {
     p.status[0] = n_invalid;
-    p.status[1] = *lds_counter;
+    p.status[1] = overflow ? 0 : *lds_counter;
+    p.status[2] = overflow ? 1 : 0;
   }
 }
 
@@ -118,24 +136,26 @@ __device__ __forceinline__ void tables_from_ids_block(const int32_t *__restrict_
   int *others = g + E + 1;     // [E]  several source ranks only
   int *pre = others + E;       // [E]
   int *misc = pre + E;         // [2]
+  __shared__ unsigned long long others_rows;
   const bool multi = p.source_count != nullptr;
   for (int e = tid; e < E; e += nthreads) {
     total[e] = 0;
     others[e] = 0;
     pre[e] = 0;
   }
-  if (tid == 0) misc[0] = 0;
+  if (tid == 0) misc[0] = 0, others_rows = 0;
   __syncthreads();
   for (int i = tid; i < d.N; i += nthreads) {
     const int e = K[i];
     if (e >= 0 && e < E) atomicAdd(&total[e], 1);
     else if (e != -1) atomicAdd(&misc[0], 1);
   }
-  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E);
+  if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E, &others_rows);
   __syncthreads();
   if (tid < kWave) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
   __syncthreads();
-  write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, misc[0], misc + 1);
+  write_plan_tables(total, multi ? others : nullptr, multi ? pre : nullptr, g, d, p, misc[0], misc + 1,
+                    multi && rows_overflow(others_rows, g[E]));
 }
 
 }  // namespace moe_rbf

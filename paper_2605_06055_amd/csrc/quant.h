@@ -1,5 +1,5 @@
 // Row-wise quantisation of a token row for the quantised dispatch (paper, Section 5.2, end of "Prefill
-// Dispatch": with row-wise quantisation the scales go to a parallel scale tensor in the same row order).
+// Dispatch"): row scales are kept in a separate float array indexed by window row.
 // The paper names no format; this library uses OCP FP8 E4M3 codes with one fp32 scale per row:
 //   amax = max |x| over the row, scale = amax / 448 (stored), q = e4m3(x * (448 / amax)), nearest even;
 //   an all-zero row gets scale 1.

@@ -84,25 +84,3 @@ class MoeLayer:
                 raise B.MoeError(rc, "moe_combine")
 
         return dispatch, combine
-
-    def standin_expert(self, topk_idx, scale):
-        """Stand-in for the expert FFNs, outside the library: every placed row times its expert's
-        scalar, rounded to storage (torch ops; not part of the measured path)."""
-        import torch
-        E = self.shape.E
-        n = int(self.plan.expert_offset[E].item()) if self.shape.region_stride_rows == 0 else self.rows
-        if n == 0:
-            return
-        # expert id of every window row from the offsets (rows past an expert's block keep scale 0)
-        off = self.plan.expert_offset[:E].long()
-        cnt = self.plan.expert_count.long()
-        row_scale = torch.zeros(self.rows, dtype=torch.float32, device=self.window.device)
-        ids = torch.repeat_interleave(torch.arange(E, device=off.device), cnt)
-        pos = torch.repeat_interleave(off, cnt) + (torch.arange(ids.numel(), device=off.device)
-                                                   - torch.repeat_interleave(torch.cumsum(cnt, 0) - cnt, cnt))
-        keep = pos < self.rows
-        row_scale[pos[keep]] = scale[ids[keep]]
-        step = max(1, (1 << 27) // self.shape.H)
-        for r0 in range(0, self.rows, step):
-            r1 = min(self.rows, r0 + step)
-            self.expert_out[r0:r1] = (self.window[r0:r1].float() * row_scale[r0:r1, None]).to(self.torch_dtype)

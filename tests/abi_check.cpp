@@ -79,21 +79,21 @@ static int run(int schedule, int T, int H, int k, int E, int R) {
   MOE_OK_(moe_dispatch(&sh, dX, dK, &pl, dWin, st));
   MOE_OK_(moe_combine(&sh, dWin, dW, &pl, dY, st));                         // identity expert: window is its own output
 
-  std::vector<int32_t> row_map(N), status(2);
+  std::vector<int32_t> row_map(N), status(3);
   std::vector<uint16_t> win((size_t)rows * H), Y(X.size());
   HIP_OK(hipMemcpyAsync(row_map.data(), pl.row_map, N * 4, hipMemcpyDeviceToHost, st));
-  HIP_OK(hipMemcpyAsync(status.data(), pl.status, 8, hipMemcpyDeviceToHost, st));
+  HIP_OK(hipMemcpyAsync(status.data(), pl.status, 12, hipMemcpyDeviceToHost, st));
   HIP_OK(hipMemcpyAsync(win.data(), dWin, win.size() * 2, hipMemcpyDeviceToHost, st));
   HIP_OK(hipMemcpyAsync(Y.data(), dY, Y.size() * 2, hipMemcpyDeviceToHost, st));
   HIP_OK(hipStreamSynchronize(st));
 
-  std::vector<int32_t> ce(E), cr(R), eo(E + 1), rb(R + 1), s(N), rm(N), rst(2);
+  std::vector<int32_t> ce(E), cr(R), eo(E + 1), rb(R + 1), s(N), rm(N), rst(3);
   moe_ref_plan(T, k, E, R, 0, K.data(), ce.data(), cr.data(), eo.data(), rb.data(), s.data(), rm.data(), rst.data());
   std::vector<uint16_t> rwin((size_t)rows * H, 0), rY(X.size());
   moe_ref_dispatch(T, H, k, 2, X.data(), rm.data(), rwin.data());
   moe_ref_combine(T, H, k, MOE_DTYPE_BF16, rwin.data(), W.data(), rm.data(), rY.data());
   if (row_map != rm) return std::printf("row_map differs (schedule %d)\n", schedule), 1;
-  if (status[0] != rst[0] || status[1] != rst[1]) return std::printf("status differs\n"), 1;
+  if (status[0] != rst[0] || status[1] != rst[1] || status[2] != rst[2]) return std::printf("status differs\n"), 1;
   if (std::memcmp(win.data(), rwin.data(), win.size() * 2)) return std::printf("window differs\n"), 1;
   for (size_t i = 0; i < Y.size(); ++i) {
     const int d = (int)Y[i] - (int)rY[i];                                  // all values positive: plain code distance

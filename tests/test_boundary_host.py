@@ -117,7 +117,7 @@ def test_pointer_alignment():
     assert code(moe.moe_plan, s, 0x104, fake_plan(), 0) == -3
     assert code(moe.moe_plan, s, 0x100, fake_plan(row_map=0x6004), 0) == -3
     assert code(moe.moe_plan, s, 0x100, fake_plan(send_idx=0x5008), 0) == -3
-    assert code(moe.moe_plan, s, 0x100, fake_plan(workspace=0x8001), 0) == -3
+    assert code(moe.moe_plan, shape(T=4000, **PRE), 0x100, fake_plan(workspace=0x8001), 0) == -3
     assert code(moe.moe_plan, s, 0x100, fake_plan(source_count=0x9004), 0) == -3
     assert code(moe.moe_plan, s, 0x100, fake_plan(recv_offset=0x9008), 0) == -3
     assert code(moe.moe_dispatch, s, 0x108, None, fake_plan(), 0x200, 0) == -3
@@ -127,10 +127,30 @@ def test_pointer_alignment():
 
 
 def test_workspace():
-    s = shape(**PRE)
+    # batches above 12288 branches are planned in two launches that hand tile histograms over in the workspace
+    s = shape(T=4000, **PRE)
     need = moe.moe_workspace_bytes(s)
+    assert need >= 16 * (16 + 1) * 4
     assert code(moe.moe_plan, s, 0x100, fake_plan(workspace=None), 0) == -5
     assert code(moe.moe_plan, s, 0x100, fake_plan(workspace_bytes=need - 1), 0) == -5
+    assert code(moe.moe_plan, s, 0x100, fake_plan(workspace=0x8008, workspace_bytes=need), 0) == -3
+
+
+def test_overlapping_buffers():
+    """x / window and y / expert_out must not share a byte; the extents are known on the host."""
+    s = shape(**PRE)                                   # T=64, H=256 bf16: x and y are 32768 B, the window 131072 B
+    xb, wb = 64 * 256 * 2, 64 * 4 * 256 * 2
+    base = 0x100000
+    for x, win in ((base, base), (base, base + xb - 16), (base + wb - 16, base), (base + 4096, base)):
+        assert code(moe.moe_dispatch, s, x, None, fake_plan(), win, 0) == -7, (x, win)
+        assert code(moe.moe_combine, s, win, 0x100, fake_plan(), x, 0) == -7, (x, win)
+    # fixed stride: the window extent is R * stride rows
+    wide = shape(region_stride_rows=1000, **PRE)
+    assert code(moe.moe_dispatch, wide, base + 4 * 1000 * 512 - 16, None, fake_plan(), base, 0) == -7
+    # quantised dispatch: codes, scales and x are three separate ranges
+    assert code(moe.moe_dispatch_quant, s, base, None, fake_plan(), base + 16, 0x900000, 0) == -7
+    assert code(moe.moe_dispatch_quant, s, base, None, fake_plan(), 0x900000, base + xb - 16, 0) == -7
+    assert code(moe.moe_dispatch_quant, s, base, None, fake_plan(), 0x900000, 0x900000 + 256, 0) == -7
 
 
 def test_empty_prefill_dispatch_and_combine_are_noops():
@@ -151,5 +171,5 @@ def test_quantised_dispatch_validation():
 
 
 def test_strerror():
-    texts = {moe.moe_strerror(c) for c in range(0, -7, -1)}
-    assert len(texts) == 7 and moe.moe_strerror(-99) == "unknown status"
+    texts = {moe.moe_strerror(c) for c in range(0, -8, -1)}
+    assert len(texts) == 8 and moe.moe_strerror(-99) == "unknown status"

@@ -72,7 +72,7 @@ def run_case(moe, X, K, W, scale, E, R, schedule, stride=0, label=""):
     N = T * k
     got = dict(c_exp=to_host(p.expert_count), c_rank=to_host(p.rank_count), expert_offset=to_host(p.expert_offset),
                region_base=to_host(p.region_base), s=to_host(p.send_idx)[:N].reshape(T, k),
-               row_map=to_host(p.row_map)[:N].reshape(T, k), status=to_host(p.status)[:2])
+               row_map=to_host(p.row_map)[:N].reshape(T, k), status=to_host(p.status)[:3])
     assert np.array_equal(got["c_exp"], ref.c_exp), "expert_count"
     assert np.array_equal(got["c_rank"], ref.c_rank), "rank_count"
     assert np.array_equal(got["expert_offset"], ref.expert_offset), "expert_offset"
@@ -320,7 +320,7 @@ def run_multi(moe, cfg, M, me, schedule, stride=0, seed=0):
     assert np.array_equal(to_host(p.recv_offset), ref.recv_offset)
     assert np.array_equal(to_host(p.send_idx)[:T * k].reshape(T, k), ref.s)
     assert np.array_equal(to_host(p.row_map)[:T * k].reshape(T, k), ref.row_map)
-    assert np.array_equal(to_host(p.status)[:2], ref.status)
+    assert np.array_equal(to_host(p.status)[:3], ref.status)
     ref_window = oracle.dispatch(w.X, ref.row_map, rows, fill=fill)        # other sources' rows stay untouched
     assert to_host(layer.window)[:rows].tobytes() == ref_window.tobytes()
     Yexp = oracle.expert_standin(ref_window, w.K, ref.row_map, w.scale)

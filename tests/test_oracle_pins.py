@@ -73,7 +73,7 @@ def check_golden():
         assert pl.expert_offset.tolist() == c["expert_offset"], case
         assert pl.region_base.tolist() == c["region_base"], case
         assert pl.row_map.tolist() == c["row_map"], case
-        assert pl.status.tolist() == c["status"], case
+        assert pl.status.tolist() == c["status"] + [0], case
         if "s" in c:
             assert pl.s.tolist() == c["s"], case
         window = oracle.dispatch(X, pl.row_map, pl.window_rows)
@@ -121,7 +121,7 @@ def check_plan_against_library(seed=0):
         assert np.all(np.diff(flat[by_row]) >= 0)
         same = np.diff(flat[by_row]) == 0
         assert np.all(np.diff(by_row)[same] > 0)
-        assert np.array_equal(pl.status, [0, 0])
+        assert np.array_equal(pl.status, [0, 0, 0])
 
 
 def check_masked_and_invalid(seed=1):
@@ -297,9 +297,10 @@ def check_golden_multi():
     for case in ("multi_source", "multi_source_stride_8"):
         c = g[case]
         pl = oracle.plan_multi(K, np.asarray(c["M"], np.int32), c["me"], E, R, c.get("stride", 0))
-        for key in ("c_exp", "c_rank", "expert_offset", "region_base", "row_map", "status", "o_all", "recv_count",
+        for key in ("c_exp", "c_rank", "expert_offset", "region_base", "row_map", "o_all", "recv_count",
                     "recv_offset"):
             assert getattr(pl, key).tolist() == c[key], (case, key)
+        assert pl.status.tolist() == c["status"] + [0], case
         window = oracle.dispatch(X, pl.row_map, pl.window_rows)
         Yexp = oracle.expert_standin(window, K, pl.row_map, scale)
         assert np.array_equal(unbf16(oracle.combine(Yexp, W, pl.row_map)), np.asarray(c["Y"], np.float32)), case
@@ -352,6 +353,42 @@ def check_multi_against_library(seed=6):
         assert np.array_equal(pf.row_map.reshape(-1), np.where(dropped, -1, wantf)) and pf.status[1] == dropped.sum()
 
 
+def check_row_total_limit(seed=8):
+    """Rows are int32.  Blocks of all sources that together hold 2^31 rows or more cannot be laid out:
+    status[2] = 1 and nothing is placed; one row fewer is an ordinary plan whose last block ends at 2^31 - 1."""
+    rng = np.random.default_rng(seed)
+    T, k, E, R = 9, 3, 8, 4
+    K = wl.random_routing(rng, T, k, E, p_masked=0.1, p_invalid=0.1)
+    single = oracle.plan(K, E, R)
+    own = int(single.c_exp.sum())
+    for me in (0, 2):
+        for excess in (-1, 0, 5, 2 ** 32 + 7):                  # total rows = 2^31 + excess
+            M = np.zeros((R, E), np.int64)
+            M[me] = 77                                           # own row of M is ignored
+            others = 2 ** 31 + excess - own
+            rows = [r for r in range(R) if r != me]
+            per = others // (len(rows) * E)
+            assert per < 2 ** 31
+            for r in rows:
+                M[r] = per
+            M[rows[0], E - 1] += others - per * len(rows) * E
+            assert M[rows[0], E - 1] < 2 ** 31
+            pl = oracle.plan_multi(K, M.astype(np.int32), me, E, R)
+            assert np.array_equal(pl.c_exp, single.c_exp) and np.array_equal(pl.c_rank, single.c_rank)
+            assert np.array_equal(pl.s, single.s)
+            if excess >= 0:
+                assert pl.status.tolist() == [int(single.status[0]), 0, 1], (me, excess)
+                assert np.all(pl.row_map == -1)
+            else:
+                assert pl.status.tolist() == [int(single.status[0]), 0, 0]
+                full = M.copy()
+                full[me] = single.c_exp
+                assert pl.expert_offset[E] == 2 ** 31 - 1 == full.sum()
+                assert np.array_equal(pl.recv_offset.astype(np.int64), np.concatenate([[0], np.cumsum(full.sum(0))]))
+                placed = pl.row_map.reshape(-1)[pl.s.reshape(-1) >= 0]
+                assert placed.min() >= 0 and len(np.unique(placed)) == own
+
+
 def check_quantised(seed=7):
     """Row-wise quantised dispatch: hand-worked codes, torch's float8_e4m3fn conversion as the library step,
     exact scales, and the dequantisation error bound of the format."""
@@ -400,7 +437,7 @@ def check_quantised(seed=7):
     assert np.all(np.abs(deq - x[src]) <= amax[src][:, None] * (16.0 / 448 + 1e-6))
 
 
-PINS = [check_golden, check_golden_multi, check_quantised, check_multi_against_library, check_plan_against_library, check_masked_and_invalid, check_fixed_stride, check_dispatch,
+PINS = [check_golden, check_golden_multi, check_row_total_limit, check_quantised, check_multi_against_library, check_plan_against_library, check_masked_and_invalid, check_fixed_stride, check_dispatch,
         check_combine, check_accumulation_order, check_rounding]
 
 
@@ -482,6 +519,8 @@ MUTANTS = {
     "stride_keeps_overflow": ("if (region_stride_rows > 0 && row >= region_base[e / Er + 1]) {",
                               "if (region_stride_rows > 0 && row > region_base[e / Er + 1]) {"),
 }
+MUTANTS["row_total_limit_off_by_one"] = ("if (all_rows >= 2147483648LL) {", "if (all_rows > 2147483648LL) {")
+MUTANTS["row_total_in_int32"] = ("  int64_t all_rows = 0;", "  int32_t all_rows = 0;")
 MUTANTS["multi_own_row_not_replaced"] = ("const int32_t m = r == me ? c_exp[e] : M[(int64_t)r * E + e];",
                                          "const int32_t m = M[(int64_t)r * E + e];")
 MUTANTS["multi_sources_reversed"] = ("      for (int32_t r = 0; r < R; ++r) {\n        const int32_t m = r == me",

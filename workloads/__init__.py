@@ -3,7 +3,8 @@
 This module is shared by the CPU oracle's tests and by the HIP path's tests and
 benchmark.  It only *draws inputs* -- hidden states X, routing ids K, gate
 weights W and per-expert stand-in scales -- and holds none of the method's
-arithmetic: no counting, no offsets, no placement, no reduction.
+arithmetic: no offsets, no placement, no reduction.  (The count matrix of synthetic
+peer ranks, an INPUT of the several-sources plan, is tallied here with numpy's bincount.)
 
 Shapes follow the paper's notation (Section 5.1): T tokens, hidden size H,
 routing degree k, E experts spread over R rank regions (E_r = E / R experts
@@ -134,14 +135,7 @@ def make(cfg: Config, seed: Optional[int] = None) -> Workload:
     rng = np.random.default_rng(cfg.seed if seed is None else seed)
     T, H, k, E = cfg.T, cfg.H, cfg.k, cfg.E
     X = _draw_hidden(rng, T, H, cfg.dtype)
-    if cfg.routing == "uniform":
-        K = _topk_uniform(rng, T, k, E)
-    elif cfg.routing == "zipf":
-        K = _topk_zipf(rng, T, k, E, cfg.zipf_s)
-    elif cfg.routing == "group_limited":
-        K = _topk_group_limited(rng, T, k, E, cfg.n_groups, cfg.groups_per_token)
-    else:
-        raise ValueError(cfg.routing)
+    K = draw_routing(cfg, rng)
     logits = rng.standard_normal((T, k))
     w = np.exp(logits - logits.max(axis=1, keepdims=True)) if T else logits
     W = (w / w.sum(axis=1, keepdims=True)).astype(np.float32) if T else np.zeros((0, k), np.float32)
@@ -150,6 +144,30 @@ def make(cfg: Config, seed: Optional[int] = None) -> Workload:
     else:
         scale = rng.uniform(0.5, 1.5, size=E).astype(np.float32)
     return Workload(cfg, X, np.ascontiguousarray(K.reshape(T, k)), np.ascontiguousarray(W), scale)
+
+
+def draw_routing(cfg: Config, rng: np.random.Generator) -> np.ndarray:
+    """Routing ids [T,k] of ``cfg``'s routing law from ``rng`` (no hidden states are drawn)."""
+    T, k, E = cfg.T, cfg.k, cfg.E
+    if cfg.routing == "uniform":
+        return _topk_uniform(rng, T, k, E)
+    if cfg.routing == "zipf":
+        return _topk_zipf(rng, T, k, E, cfg.zipf_s)
+    if cfg.routing == "group_limited":
+        return _topk_group_limited(rng, T, k, E, cfg.n_groups, cfg.groups_per_token)
+    raise ValueError(cfg.routing)
+
+
+def source_count_matrix(cfg: Config, sources: int, seed: int = 1000) -> np.ndarray:
+    """Gathered count matrix M[R,E] (int32) for a run as one of several source ranks: rows 0..sources-1
+    hold the per-expert branch counts of an independent draw of ``cfg``'s routing (every source rank routes
+    T tokens like this one), the remaining rows are zero.  Input synthesis only: counting the ids of a
+    synthetic peer is what the count exchange would deliver, not a step of the method under test."""
+    M = np.zeros((cfg.R, cfg.E), np.int32)
+    for r in range(min(sources, cfg.R)):
+        K = draw_routing(cfg, np.random.default_rng(seed + r))
+        M[r] = np.bincount(K.reshape(-1), minlength=cfg.E)
+    return M
 
 
 def random_routing(rng: np.random.Generator, T: int, k: int, E: int, *, distinct: bool = False,
