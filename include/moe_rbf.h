@@ -70,6 +70,7 @@ enum moe_status {
 #define MOE_AUTO_DECODE_MAX_BRANCHES 4096
 #define MOE_DECODE_MAX_BRANCHES 8192
 #define MOE_PLAN_SINGLE_LAUNCH_MAX_BRANCHES 12288 /* up to here moe_plan is one launch and ignores plan->workspace */
+#define MOE_STATIC_SCRATCH_BYTES (1u << 20)       /* device scratch held by the library for moe_plan_static */
 
 typedef struct moe_shape {
   int32_t T;                  /* tokens (0 is legal: counts are zeroed, nothing else happens) */
@@ -135,6 +136,20 @@ int moe_resolve_schedule(const moe_shape *shape, int32_t *out_schedule);
  *   Writes every array of `plan` (send_idx only if non-NULL) and zero-initialises status itself.
  *   Moves no payload.  Results do not depend on the launch configuration. */
 int moe_plan(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream);
+
+/* moe_plan for callers that cannot allocate device memory or hand a workspace over: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results and the same
+ * kernels as moe_plan, but plan->workspace and plan->workspace_bytes are ignored: the scratch (per-tile
+ * histograms) lives in a device array of MOE_STATIC_SCRATCH_BYTES that is part of the library image, one copy
+ * per device, held until the process ends.  The call allocates and frees nothing.
+ *   Limit: MOE_ERR_WORKSPACE if moe_workspace_bytes(shape) > MOE_STATIC_SCRATCH_BYTES (with E <= 510 every
+ *   shape fits; E = 1024 fits up to 261120 branches); decided on the host before anything is enqueued.
+ *   The first call on a device looks the array's device address up (hipGetSymbolAddress, no allocation);
+ *   make that first call outside stream capture.  A failed lookup returns MOE_ERR_LAUNCH.
+ *   Every call on a device shares that device's array.  Nothing in it has to start at zero (each call writes
+ *   every word before reading it), but two calls that overlap in time on one device, on different streams,
+ *   race on it: serialise them, or use moe_plan with separate workspaces. */
+int moe_plan_static(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream);
 
 /* Dispatch (paper, Section 5.2 "Prefill Dispatch" / Section 5.3 "Decode Dispatch"; first loop of
  * Algorithms 1 and 2): window[row_map[t,j], :] = X[t, :] for every placed branch.

@@ -9,6 +9,6 @@ binding's entry points raises.
 from .binding import (  # noqa: F401
     MOE_DTYPE_BF16, MOE_DTYPE_F32, MOE_SCHEDULE_AUTO, MOE_SCHEDULE_DECODE, MOE_SCHEDULE_PREFILL,
     MoeError, MoePlan, MoeShape, library_path, load_library, moe_combine, moe_dispatch, moe_dispatch_quant,
-    moe_plan,
+    moe_plan, moe_plan_static,
     moe_resolve_schedule, moe_strerror, moe_window_rows, moe_workspace_bytes,
 )

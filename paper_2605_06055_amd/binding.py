@@ -69,6 +69,7 @@ def load_library():
         lib.moe_window_rows.argtypes = [shp, ctypes.POINTER(ctypes.c_int64)]
         lib.moe_resolve_schedule.argtypes = [shp, i32p]
         lib.moe_plan.argtypes = [shp, vp, plp, vp]
+        lib.moe_plan_static.argtypes = [shp, vp, plp, vp]
         lib.moe_dispatch.argtypes = [shp, vp, vp, plp, vp, vp]
         lib.moe_combine.argtypes = [shp, vp, vp, plp, vp, vp]
         lib.moe_dispatch_quant.argtypes = [shp, vp, vp, plp, vp, vp, vp]
@@ -76,7 +77,8 @@ def load_library():
         lib.moe_strerror.restype = ctypes.c_char_p
         lib.moe_last_launch_error.argtypes = []
         lib.moe_last_launch_error.restype = ctypes.c_char_p
-        for f in ("moe_workspace_bytes", "moe_window_rows", "moe_resolve_schedule", "moe_plan", "moe_dispatch",
+        for f in ("moe_workspace_bytes", "moe_window_rows", "moe_resolve_schedule", "moe_plan", "moe_plan_static",
+                  "moe_dispatch",
                   "moe_dispatch_quant", "moe_combine"):
             getattr(lib, f).restype = ctypes.c_int
         _lib = lib
@@ -161,6 +163,12 @@ def moe_plan(shape: MoeShape, topk_idx, plan, stream=None) -> None:
     ps = _plan_struct(plan)
     _check(load_library().moe_plan(ctypes.byref(shape), _ptr(topk_idx), ctypes.byref(ps), _stream(stream)),
            "moe_plan")
+
+
+def moe_plan_static(shape: MoeShape, topk_idx, plan, stream=None) -> None:
+    ps = _plan_struct(plan)
+    _check(load_library().moe_plan_static(ctypes.byref(shape), _ptr(topk_idx), ctypes.byref(ps), _stream(stream)),
+           "moe_plan_static")
 
 
 def moe_dispatch(shape: MoeShape, x, topk_idx, plan, window, stream=None) -> None:

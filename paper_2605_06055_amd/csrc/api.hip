@@ -2,10 +2,17 @@
 // caller's stream.  Nothing here allocates, copies between host and device, or synchronises.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "launch.h"
 #include "moe_rbf.h"
 
 using namespace moe_rbf;
+
+// Scratch of moe_plan_static: the per-tile histograms that moe_plan keeps in the caller's plan->workspace.
+// One copy per device, held until the process ends.  In host code this name is only a stand-in for the
+// device array; its device address comes from hipGetSymbolAddress (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -107,7 +114,29 @@ inline uint64_t window_bytes(const Dims &d) {
   return rows * (uint64_t)d.H16 * 16u;
 }
 
-int plan_call(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream) {
+// Device address of `scratch` on the current device, resolved once per device.
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return launch_status(e);
+  if (dev < 0 || dev >= kMaxDevices) return launch_status(hipErrorInvalidDevice);
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return launch_status(e);
+    if (!p) return launch_status(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread resolves the same address
+  }
+  *out = p;
+  return MOE_OK;
+}
+
+// Common body of moe_plan and moe_plan_static.  own_scratch: the tile histograms go to the library's
+// static device array instead of plan->workspace.
+int plan_call(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream, bool own_scratch) {
   Dims d;
   PlanView v;
   int rc = check_shape(shape, &d);
@@ -121,9 +150,17 @@ int plan_call(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan,
   if (d.T == 0) return launch_status(launch_plan_empty(d, v, s));
   int32_t *tile_hist = nullptr;
   if (plan_uses_workspace(d.N)) {
-    if (!plan->workspace || plan->workspace_bytes < workspace_need(shape)) return MOE_ERR_WORKSPACE;
-    if (!aligned16(plan->workspace)) return MOE_ERR_ALIGN;
-    tile_hist = (int32_t *)plan->workspace;
+    if (own_scratch) {
+      if (workspace_need(shape) > (size_t)MOE_STATIC_SCRATCH_BYTES) return MOE_ERR_WORKSPACE;
+      void *p = nullptr;
+      rc = static_scratch(&p);
+      if (rc != MOE_OK) return rc;
+      tile_hist = (int32_t *)p;
+    } else {
+      if (!plan->workspace || plan->workspace_bytes < workspace_need(shape)) return MOE_ERR_WORKSPACE;
+      if (!aligned16(plan->workspace)) return MOE_ERR_ALIGN;
+      tile_hist = (int32_t *)plan->workspace;
+    }
   }
   return launch_status(launch_plan(d, topk_idx, v, tile_hist, s));
 }
@@ -158,7 +195,11 @@ int moe_resolve_schedule(const moe_shape *shape, int32_t *out_schedule) {
 }
 
 int moe_plan(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream) {
-  return plan_call(shape, topk_idx, plan, stream);
+  return plan_call(shape, topk_idx, plan, stream, false);
+}
+
+int moe_plan_static(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, void *stream) {
+  return plan_call(shape, topk_idx, plan, stream, true);
 }
 
 int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx, moe_plan_t *plan, void *window,

@@ -136,6 +136,18 @@ def test_workspace():
     assert code(moe.moe_plan, s, 0x100, fake_plan(workspace=0x8008, workspace_bytes=need), 0) == -3
 
 
+def test_static_scratch_plan_limits():
+    """moe_plan_static ignores the workspace fields and rejects shapes whose tile histograms exceed its
+    fixed device array (1 MiB), on the host, like every other argument error."""
+    big_e = shape(T=40000, k=8, E=1024, R=64, **PRE)          # 320000 branches -> 313 tiles x 1025 words
+    assert moe.moe_workspace_bytes(big_e) > (1 << 20)
+    assert code(moe.moe_plan_static, big_e, 0x100, fake_plan(workspace=None, workspace_bytes=0), 0) == -5
+    s = shape(T=4000, **PRE)
+    assert code(moe.moe_plan_static, s, None, fake_plan(workspace=None, workspace_bytes=0), 0) == -1
+    assert code(moe.moe_plan_static, s, 0x104, fake_plan(workspace=None, workspace_bytes=0), 0) == -3
+    assert code(moe.moe_plan_static, shape(E=10, **PRE), 0x100, fake_plan(), 0) == -2
+
+
 def test_overlapping_buffers():
     """x / window and y / expert_out must not share a byte; the extents are known on the host."""
     s = shape(**PRE)                                   # T=64, H=256 bf16: x and y are 32768 B, the window 131072 B
