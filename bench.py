@@ -159,7 +159,7 @@ def graph_time_ms(fn, n_calls, replays):
 
 
 def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1, quant=False, bound=False,
-            reuse_plan=False):
+            reuse_plan=False, graph_too=False):
     import paper_2605_06055_amd as moe
     s = Sets(cfg, n_sets, schedule, sources, quant)
     if reuse_plan:                       # the constructor has planned every buffer set once
@@ -220,6 +220,13 @@ def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1, 
     kern["combine_gbs"] = half / kern["combine_us"] / 1e3
     res["kernels"] = kern
     res["half_bytes"] = half
+    if graph_too and not use_graph:
+        # the same layers as one captured graph (kernel nodes only), replayed: what a serving loop that
+        # captures its layers would see (no host launch work between the kernels)
+        per_graph = max(n_sets, 10)
+        gms, g = graph_time_ms(s.step, per_graph, max(2, steps // per_graph))
+        res["us_per_layer_graph"] = gms * 1e3
+        del g
     return res
 
 
@@ -246,13 +253,61 @@ def copy_ceiling():
     return out
 
 
+def mix_ceilings(cfg, iters=30):
+    """What the memory system sustains for the two access mixes of the path at this workload's shape,
+    measured with plain kernels that share nothing with the library (ceilings/stream_mix.hip):
+    8 reads : 1 write (combine's mix) and 1 read : 8 writes (dispatch's mix) of 16-byte vectors, once with
+    purely sequential rows and once with the rows scattered over the expert blocks exactly as this workload's
+    routing scatters them; plus read-only and write-only streams.  Each figure is the better of two launch
+    forms (one workgroup per 2 KB unit / a persistent grid).  GB/s over bytes read + written; loops of
+    identical launches, i.e. the conditions of `kernels` (not of `kernels_in_sequence`)."""
+    import numpy as np
+    import torch
+    import ceilings
+    import workloads as wl
+    T, H, k = cfg.T, cfg.H, cfg.k
+    assert k == 8
+    cols = H * cfg.elem_bytes // 16
+    big = torch.empty((T * k, H), dtype=torch.bfloat16, device="cuda").fill_(1.0)
+    small = torch.empty((T, H), dtype=torch.bfloat16, device="cuda").fill_(2.0)
+    K = wl.draw_routing(cfg, np.random.default_rng(cfg.seed)).reshape(-1)
+    order = np.argsort(K, kind="stable")                      # branches in window-row order (expert blocks)
+    scattered = np.empty(T * k, np.int32)
+    scattered[order] = np.arange(T * k, dtype=np.int32)
+    assert scattered.min() == 0 and scattered.max() == T * k - 1
+    tables = {"sequential": torch.arange(T * k, dtype=torch.int32, device="cuda"),
+              "scattered": torch.from_numpy(scattered).cuda()}
+    total = (1 + k) * T * H * cfg.elem_bytes
+    out = {"bytes_per_launch": total, "of": "better of one workgroup per (row, 128-vector chunk) and a "
+           "persistent grid of 2048 workgroups; nontemporal 16-byte accesses"}
+    for name, kind, src, dst in (("read8_write1", ceilings.GATHER, big, small),
+                                 ("read1_write8", ceilings.SCATTER, small, big)):
+        for tname, table in tables.items():
+            best = None
+            for grid in (0, 2048):
+                fn = lambda i: ceilings.mix(kind, k, src, table, dst, T, cols, grid=grid)
+                fn(0)
+                ms = event_time_ms(fn, iters)
+                best = ms if best is None else min(best, ms)
+            out[f"{name}_{tname}_us"] = round(best * 1e3, 2)
+            out[f"{name}_{tname}_GBps"] = round(total / best / 1e6, 1)
+    sink = torch.zeros(16, dtype=torch.int32, device="cuda")
+    ceilings.read(big, sink)
+    ms = event_time_ms(lambda i: ceilings.read(big, sink), iters)
+    out["read_only_GBps"] = round(big.numel() * 2 / ms / 1e6, 1)
+    ceilings.write(big)
+    ms = event_time_ms(lambda i: ceilings.write(big), iters)
+    out["write_only_GBps"] = round(big.numel() * 2 / ms / 1e6, 1)
+    return out
+
+
 def cpu_baseline(cfg, budget_s=10.0):
     """The oracle as it stands on a bounded sample of the same workload: single thread (the headline
     figure) and, beside it, the same source built with OpenMP so that the token loops of dispatch and
     combine use every host core (the plan stays serial)."""
     import oracle
     import workloads as wl
-    T = min(cfg.T, 2048)                           # a slice of the batch keeps the leg to seconds
+    T = min(cfg.T, 4096)                           # the whole headline batch; a slice of the larger workloads
     sub = cfg.with_(T=T)
     w = wl.make(sub)
 
@@ -272,8 +327,8 @@ def cpu_baseline(cfg, budget_s=10.0):
         threads = oracle.threads()
         per_all, reps_all = timed(budget_s / 2)
     return {"value": sub.payload_bytes / per / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {T} tokens of the workload (plan+dispatch+combine, identity expert), "
-                      f"{reps} repetitions, {per * 1e3:.1f} ms each",
+            "sample": (f"the whole batch of {T} tokens" if T == cfg.T else f"first {T} tokens of the workload")
+                      + f" (plan+dispatch+combine, identity expert), {reps} repetitions, {per * 1e3:.1f} ms each",
             "all_cores": {"value": round(sub.payload_bytes / per_all / 1e9, 3), "unit": "GB/s", "cores": threads,
                           "sample": f"same sample, {reps_all} repetitions, {per_all * 1e3:.1f} ms each"},
             "host_cpus": os.cpu_count()}
@@ -281,12 +336,29 @@ def cpu_baseline(cfg, budget_s=10.0):
 
 def traffic_for(kernel):
     """HBM bytes per launch measured with rocprofv3 --pmc (committed summary of two counter runs,
-    scaled by a plain copy of known size), or None when no summary covers this kernel and workload."""
+    scaled by a plain copy of known size), or None when no summary covers this kernel and workload.
+    Returns (bytes, where the figure comes from)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
-        return json.load(open(path))[kernel]["total_bytes"]
+        table = json.load(open(path))
+        return table[kernel]["total_bytes"], table.get("_source", "profiles/hbm_traffic.json")
     except (OSError, ValueError, KeyError):
-        return None
+        return None, None
+
+
+def compact(res, cfg):
+    """One workload's figures for the JSON line."""
+    pct = res["wall_us_per_layer"]
+    out = {"workload": DESCR[cfg.name], "us_per_layer": round(res["us_per_layer"], 2),
+           "value": round(res["gbs"], 1), "unit": "GB/s",
+           "frac_of_hbm_peak": round(res["gbs"] / HBM_PEAK_GBS, 4),
+           "us_per_layer_p50": pct["p50"],
+           "frac_of_hbm_peak_p50": round(cfg.payload_bytes / pct["p50"] / 1e3 / HBM_PEAK_GBS, 4),
+           "kernels": rounded(res["kernels"]), "kernels_in_sequence": res.get("kernels_in_sequence")}
+    if "us_per_layer_graph" in res:
+        out["us_per_layer_graph"] = round(res["us_per_layer_graph"], 2)
+        out["frac_of_hbm_peak_graph"] = round(cfg.payload_bytes / res["us_per_layer_graph"] / 1e3 / HBM_PEAK_GBS, 4)
+    return out
 
 
 def main():
@@ -297,6 +369,7 @@ def main():
     ap.add_argument("--workload", default="prefill", choices=sorted(DESCR))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode T=128 leg of the headline run")
+    ap.add_argument("--no-others", action="store_true", help="skip the skewed and wide prefill workloads")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the streaming-copy ceiling measurement")
     ap.add_argument("--decode-sweep", action="store_true",
                     help="also time decode layers at the paper's Table 2 points: hidden 4096 and 7168, "
@@ -336,13 +409,19 @@ def main():
 
     cfg = wl.CONFIGS[args.workload]
     n_sets = 20 if cfg.payload_bytes < 512e6 else 1
-    main_res = measure(cfg, args.steps, args.warmup, n_sets)
+    main_res = measure(cfg, args.steps, args.warmup, n_sets, graph_too=True)
     log(f"[{args.workload}] {json.dumps(main_res)}")
 
+    # The dominant kernel and its duration come from plan -> dispatch -> combine sequences (each call between
+    # its own HIP events on the launch stream), i.e. in the cache state the layer really leaves; a loop of
+    # identical launches (`kernels`) can flatter a kernel whose input stays in the Infinity Cache.
     kern = main_res["kernels"]
-    dom = "moe_combine" if kern["combine_us"] >= kern["dispatch_us"] else "moe_dispatch"
-    dom_us = max(kern["combine_us"], kern["dispatch_us"])
+    seq = main_res.get("kernels_in_sequence") or {k: v for k, v in kern.items() if k.endswith("_us")}
+    dom = "moe_combine" if seq["combine_us"] >= seq["dispatch_us"] else "moe_dispatch"
+    dom_us = max(seq["combine_us"], seq["dispatch_us"])
     achieved = main_res["half_bytes"] / dom_us / 1e3
+    traffic, traffic_source = traffic_for(f"{dom}:{args.workload}")
+    head = compact(main_res, cfg)
     out = {
         "metric": "dispatch+combine effective HBM GB/s", "value": round(main_res["gbs"], 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(main_res["ms_per_step"], 5),
@@ -351,18 +430,44 @@ def main():
         "data": "synthetic",
         "config": {"workload": DESCR[args.workload], "schedule": main_res["schedule"], "storage": "bf16",
                    "payload_bytes_per_step": cfg.payload_bytes, "buffer_sets": n_sets},
-        "us_per_layer": round(main_res["us_per_layer"], 2),
+        "us_per_layer": head["us_per_layer"],
         "wall_us_per_layer": main_res["wall_us_per_layer"],
-        "frac_of_hbm_peak": round(main_res["gbs"] / HBM_PEAK_GBS, 4),
+        "frac_of_hbm_peak": head["frac_of_hbm_peak"],
+        "frac_of_hbm_peak_p50": head["frac_of_hbm_peak_p50"],
+        "us_per_layer_graph": head.get("us_per_layer_graph"),
+        "frac_of_hbm_peak_graph": head.get("frac_of_hbm_peak_graph"),
         "kernels": rounded(kern),
         "kernels_in_sequence": main_res.get("kernels_in_sequence"),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": traffic_for(f"{dom}:{args.workload}")},
+                     "duration_us": round(dom_us, 2),
+                     "duration_from": "HIP events around the call inside plan->dispatch->combine sequences "
+                                      "(includes the event-to-event gap); `kernels` holds back-to-back loops",
+                     "traffic": traffic, "traffic_source": traffic_source},
     }
     if not args.no_ceiling:
         out["copy_ceiling"] = copy_ceiling()
         out["frac_of_copy_ceiling"] = round(main_res["gbs"] / max(out["copy_ceiling"].values()), 4)
+        mc = mix_ceilings(cfg)
+        log(f"[mix ceilings] {json.dumps(mc)}")
+        out["mix_ceiling"] = mc
+        # like with like: the library's kernels in loops of identical launches against the plain kernels in
+        # the same kind of loop, for the scattered rows of this routing and for purely sequential rows
+        out["frac_of_mix_ceiling"] = {
+            "dispatch_vs_read1_write8_scattered": round(mc["read1_write8_scattered_us"] / kern["dispatch_us"], 4),
+            "combine_vs_read8_write1_scattered": round(mc["read8_write1_scattered_us"] / kern["combine_us"], 4),
+            "dispatch_vs_read1_write8_sequential": round(mc["read1_write8_sequential_us"] / kern["dispatch_us"], 4),
+            "combine_vs_read8_write1_sequential": round(mc["read8_write1_sequential_us"] / kern["combine_us"], 4)}
+    if args.workload == "prefill" and not args.no_others:
+        # the other two prefill workloads of the configuration list, one compact entry each
+        out["workloads"] = {}
+        for name in ("skewed", "wide"):
+            c = wl.CONFIGS[name]
+            r = measure(c, max(10, args.steps // 4), max(2, args.warmup // 4), 1)
+            log(f"[{name}] {json.dumps(r)}")
+            out["workloads"][name] = compact(r, c)
+            del r
+            torch.cuda.empty_cache()
     if args.workload == "prefill" and not args.no_decode:
         dcfg = wl.CONFIGS["decode"]
         d = measure(dcfg, max(args.steps, 400), args.warmup, 20, use_graph=True)
@@ -375,7 +480,10 @@ def main():
         log(f"[decode, eager launches from Python, pre-marshalled] {json.dumps(de)}")
         out["decode"] = {"workload": DESCR["decode"], "us_per_layer": round(d["us_per_layer"], 2),
                          "value": round(d["gbs"], 1), "unit": "GB/s",
-                         "frac_of_hbm_peak": round(d["gbs"] / HBM_PEAK_GBS, 4), "buffer_sets": d["buffer_sets"],
+                         "frac_of_hbm_peak": round(d["gbs"] / HBM_PEAK_GBS, 4),
+                         "frac_of_hbm_peak_p50": round(dcfg.payload_bytes / d["wall_us_per_layer"]["p50"] / 1e3
+                                                       / HBM_PEAK_GBS, 4),
+                         "buffer_sets": d["buffer_sets"],
                          "launch": "one HIP graph of 20 layers replayed (a layer is 2 kernels of ~5 us)",
                          "wall_us_per_layer": d["wall_us_per_layer"],
                          "us_per_layer_warm": round(dw["us_per_layer"], 2),
@@ -391,6 +499,15 @@ def main():
                          "cache": "cold: 20 disjoint buffer sets (660 MB) rotated so no step finds its lines in "
                                   "the 256 MB Infinity Cache",
                          "kernels": rounded(d["kernels"])}
+        ddom = "moe_dispatch" if d["kernels"]["dispatch_us"] >= d["kernels"]["combine_us"] else "moe_combine"
+        dus = max(d["kernels"]["dispatch_us"], d["kernels"]["combine_us"])
+        dtraffic, dsource = traffic_for(f"{ddom}:decode")
+        out["decode"]["roofline"] = {"bound": "hbm", "kernel": ddom, "achieved": round(d["half_bytes"] / dus / 1e3, 1),
+                                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                     "frac": round(d["half_bytes"] / dus / 1e3 / HBM_PEAK_GBS, 4),
+                                     "duration_us": round(dus, 2),
+                                     "duration_from": "graph replay of 20 launches of the kernel alone on cold buffers",
+                                     "traffic": dtraffic, "traffic_source": dsource}
     if args.quant:
         pc, dc = wl.CONFIGS["prefill"], wl.CONFIGS["decode"]
         qp = measure(pc, args.steps, args.warmup, 1, quant=True)

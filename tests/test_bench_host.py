@@ -37,7 +37,9 @@ def test_committed_traffic_summary_covers_the_named_workloads():
             assert e["algorithmic_bytes"] == cfg.payload_bytes // 2
             assert e["total_bytes"] == e["fetch_bytes"] + e["write_bytes"]
             assert 0.99 <= e["total_bytes"] / e["algorithmic_bytes"] <= 1.05      # no wasted re-reads
-            assert bench.traffic_for(f"{kern}:{wlname}") == e["total_bytes"]
+            got, source = bench.traffic_for(f"{kern}:{wlname}")
+            assert got == e["total_bytes"] and source == d["_source"]
+    assert bench.traffic_for("moe_combine:no such workload") == (None, None)
 
 
 def test_cpu_baseline_runs_the_oracle_on_a_bounded_sample():
