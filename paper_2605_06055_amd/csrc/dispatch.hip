@@ -65,32 +65,60 @@ __global__ __launch_bounds__(BLOCK) void dispatch_slices_kernel(const u32x4 *__r
 // registers) and one LDS exchange between its waves: no histogram, no scan, one barrier.  The two
 // counts of a slot travel packed in one word (low 16 bits: ids below e; high 16 bits: equal ids in
 // front of the branch).
-// One extra workgroup (the last) builds the histogram and writes the tables for combine and the experts.
+// One extra workgroup (the first, since it takes longest) builds the histogram and writes the tables for
+// combine and the experts.
 
-constexpr int kSlotBatch = 8;     // slots of a token ranked together
 
 // QUANT: the workgroup holds a whole row (chunks == 1), quantises it once and fans the codes and the
 // row's scale out instead of the bf16 payload.
-template <int BLOCK, int V, bool QUANT>
+// MULTI: plan->source_count is given (several source ranks); compiled apart so that the single-source
+// kernel, which is latency-bound, carries none of that code.
+// SB: slots of a token ranked together (one LDS exchange per SB slots).  The slots of a token may be split
+// over `groups` workgroups (each ranks and stores only its own slots of the chunk): more, smaller
+// workgroups spread the stores over all compute units and shorten each one's counting.
+// GROUPS is a compile-time constant so that the index arithmetic in front of the first loads stays short.
+template <int BLOCK, int V, int SB, int GROUPS, bool QUANT, bool MULTI>
 __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__restrict__ X,
                                                                 const int32_t *__restrict__ K,
                                                                 void *__restrict__ window_any,
                                                                 float *__restrict__ window_scale, Dims d, PlanView p,
-                                                                int chunks) {
+                                                                int chunks, int per_group) {
+  constexpr int groups = GROUPS;
   extern __shared__ int lds[];                                  // tables workgroup; several-sources prefix tables
-  __shared__ int part[(BLOCK / kWave) * kSlotBatch];            // per-wave packed counts of a slot batch
-  __shared__ int part_m[(BLOCK / kWave) * kSlotBatch];          // per-wave rows of the other source ranks
+  __shared__ int part[(BLOCK / kWave) * SB];            // per-wave packed counts of a slot batch
+  __shared__ int part_m[(BLOCK / kWave) * SB];          // per-wave rows of the other source ranks
   __shared__ int part_v[BLOCK / kWave];                         // per-wave number of ids inside [0,E)
   __shared__ unsigned long long others_rows;                    // rows of the other source ranks, 64-bit
   constexpr int kWaves = BLOCK / kWave;
-  if ((int)blockIdx.x == d.T * chunks) {
+  const int per_token = chunks * groups;
+  if (blockIdx.x == 0) {                 // the tables workgroup goes first: it is the longest one
     tables_from_ids_block(K, d, p, lds);
     return;
   }
+  const int b = (int)blockIdx.x - 1;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int t = blockIdx.x / chunks;
-  const int c = blockIdx.x - t * chunks;
+  // workgroup -> (token, chunk, slot group).  Workgroups go to the 8 XCDs round-robin: the workgroups of a
+  // token are given to one XCD, whose L2 then serves their re-reads of the token row (the ragged tail of
+  // tokens past a multiple of 8 is mapped plainly).
+  int t, rem;
+  {
+    const int full = (d.T & ~7) * per_token;
+    if (b >= full) {
+      t = b / per_token;
+      rem = b - t * per_token;
+    } else if (chunks == 1) {             // the usual case: compile-time divisor
+      const int q = b >> 3;
+      t = (q / GROUPS) * 8 + (b & 7);
+      rem = q % GROUPS;
+    } else {
+      const int q = b >> 3, tq = q / per_token;
+      t = tq * 8 + (b & 7);
+      rem = q - tq * per_token;
+    }
+  }
+  const int c = rem / groups, grp = rem % groups;
   const int first = t * d.k;
+  const int jg0 = grp * per_group, jg1 = min(d.k, jg0 + per_group);       // per_group: slots of a group, whole batches
 
   // everything that comes from memory is requested up front: payload, routing ids, own slots' ids
   const int col0 = c * (BLOCK * V) + tid;
@@ -99,7 +127,8 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
 #pragma unroll
   for (int x = 0; x < V; ++x) {
     const int col = col0 + x * BLOCK;
-    v[x] = col < d.H16 ? load_stream(src + col) : u32x4{0u, 0u, 0u, 0u};
+    // read once by this workgroup: streaming, unless sibling workgroups of the token read it too
+    v[x] = col < d.H16 ? (groups > 1 ? src[col] : load_stream(src + col)) : u32x4{0u, 0u, 0u, 0u};
   }
   constexpr int kIds = 4;        // ids per thread kept in registers (first kIds passes over K)
   int id[kIds];
@@ -123,8 +152,8 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
   // i.e. sums over parts of the count matrix M.  A thread owns a few columns of M and keeps, per column, the
   // sum over the other ranks and the sum over the lower ranks; a slot's two terms are then masked sums of
   // these over the workgroup (wave reduction + the LDS exchange the id counts use anyway).
-  const bool multi = p.source_count != nullptr;
-  constexpr int kCols = (MOE_MAX_EXPERTS + BLOCK - 1) / BLOCK;     // columns a thread may own
+  constexpr bool multi = MULTI;
+  constexpr int kCols = MULTI ? (MOE_MAX_EXPERTS + BLOCK - 1) / BLOCK : 1;     // columns a thread may own
   int col_all[kCols], col_pre[kCols], col_id[kCols];
 #pragma unroll
   for (int q2 = 0; q2 < kCols; ++q2) col_all[q2] = col_pre[q2] = 0, col_id[q2] = -1;
@@ -164,16 +193,16 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
   bool overflow = false;                            // rows of all sources together do not fit in int32
 
   const bool fixed = d.stride > 0;
-  for (int j0 = 0; j0 < d.k; j0 += kSlotBatch) {
-    // lane u < 8 of every wave owns slot j0+u
-    const bool own = lane < kSlotBatch && j0 + lane < d.k;
+  for (int j0 = jg0; j0 < jg1; j0 += SB) {
+    // lane u < SB of every wave owns slot j0+u
+    const bool own = lane < SB && j0 + lane < jg1;
     const int my_e = own ? K[first + j0 + lane] : -1;
     const bool my_valid = my_e >= 0 && my_e < d.E;
     const int my_rank = my_valid ? my_e / d.Er : 0;
     const int my_lo = fixed ? my_rank * d.Er : 0;
-    int e[kSlotBatch], lo[kSlotBatch], below[kSlotBatch], front[kSlotBatch];
+    int e[SB], lo[SB], below[SB], front[SB];
 #pragma unroll
-    for (int u = 0; u < kSlotBatch; ++u) {
+    for (int u = 0; u < SB; ++u) {
       e[u] = __builtin_amdgcn_readlane(my_e, u);
       lo[u] = __builtin_amdgcn_readlane(my_lo, u);
       below[u] = 0;
@@ -192,24 +221,24 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
         x = i < d.N ? K[i] : -1;
       }
       const int ahead = first + j0 - i;               // slot u is behind id i  <=>  u + ahead > 0
-      if (multi && j0 == 0) n_valid += __popcll(__ballot((unsigned)x < (unsigned)d.E));
+      if (multi && j0 == jg0) n_valid += __popcll(__ballot((unsigned)x < (unsigned)d.E));
       // ids outside [0,E) never satisfy either test: as unsigned values they are huge (or x > e)
       if (fixed) {
 #pragma unroll
-        for (int u = 0; u < kSlotBatch; ++u)
+        for (int u = 0; u < SB; ++u)
           below[u] += __popcll(__ballot((unsigned)(x - lo[u]) < (unsigned)(e[u] - lo[u])));
       } else {
 #pragma unroll
-        for (int u = 0; u < kSlotBatch; ++u) below[u] += __popcll(__ballot((unsigned)x < (unsigned)e[u]));
+        for (int u = 0; u < SB; ++u) below[u] += __popcll(__ballot((unsigned)x < (unsigned)e[u]));
       }
 #pragma unroll
-      for (int u = 0; u < kSlotBatch; ++u)
+      for (int u = 0; u < SB; ++u)
         front[u] += __popcll(__ballot(x == e[u]) & __ballot(ahead + u > 0));   // two masks, and-ed as scalars
     }
     int mine_m = 0;                                   // lane u: this wave's rows of other sources in front of slot u
     if (multi) {
 #pragma unroll
-      for (int u = 0; u < kSlotBatch; ++u) {
+      for (int u = 0; u < SB; ++u) {
         int cu = 0;
 #pragma unroll
         for (int q2 = 0; q2 < kCols; ++q2) {
@@ -220,31 +249,31 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
         mine_m = lane == u ? tot : mine_m;
       }
     }
-    if (j0 > 0) __syncthreads();                      // the previous batch's exchange has been read
+    if (j0 > jg0) __syncthreads();                      // the previous batch's exchange has been read
     {
       int mine = 0;                                   // lane u carries this wave's packed counts of slot u
 #pragma unroll
-      for (int u = 0; u < kSlotBatch; ++u) mine = lane == u ? below[u] + (front[u] << 16) : mine;
-      if (lane < kSlotBatch) {
-        part[wave * kSlotBatch + lane] = mine;
-        if (multi) part_m[wave * kSlotBatch + lane] = mine_m;
+      for (int u = 0; u < SB; ++u) mine = lane == u ? below[u] + (front[u] << 16) : mine;
+      if (lane < SB) {
+        part[wave * SB + lane] = mine;
+        if (multi) part_m[wave * SB + lane] = mine_m;
       }
-      if (multi && j0 == 0 && lane == 0) part_v[wave] = n_valid;
+      if (multi && j0 == jg0 && lane == 0) part_v[wave] = n_valid;
     }
     __syncthreads();
-    if (multi && j0 == 0) {
+    if (multi && j0 == jg0) {
       unsigned own_rows = 0;
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) own_rows += (unsigned)part_v[w];
       overflow = others_rows + own_rows >= (1ull << 31);
     }
     int packed = 0, ahead_m = 0;
-    if (lane < kSlotBatch) {
+    if (lane < SB) {
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) packed += part[w * kSlotBatch + lane];
+      for (int w = 0; w < kWaves; ++w) packed += part[w * SB + lane];
       if (multi)
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) ahead_m += part_m[w * kSlotBatch + lane];
+        for (int w = 0; w < kWaves; ++w) ahead_m += part_m[w * SB + lane];
     }
     int s = -1, row = -1;
     if (own && my_valid) {
@@ -258,7 +287,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
       p.row_map[first + j0 + lane] = row;
     }
     // fan the chunk out to this batch's destination rows
-    const int nb = min(kSlotBatch, d.k - j0);
+    const int nb = min(SB, jg1 - j0);
     for (int u = 0; u < nb; ++u) {
       const int r = __builtin_amdgcn_readlane(row, u);
       if (r < 0) continue;
@@ -363,24 +392,38 @@ hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void
   return hipErrorInvalidValue;
 }
 
-template <int V>
-static hipError_t launch_decode_dispatch_v(const Dims &d, const void *x, const int32_t *K, const PlanView &p,
-                                           void *window, hipStream_t s) {
-  constexpr int B = MOE_DECODE_BLOCK;
+template <int B, int V, int SB, int G>
+static hipError_t launch_decode_dispatch_shape(const Dims &d, const void *x, const int32_t *K, const PlanView &p,
+                                               void *window, hipStream_t s) {
   const int chunks = (d.H16 + B * V - 1) / (B * V);
+  const int per_group = ((d.k + G - 1) / G + SB - 1) / SB * SB;
   const size_t lds = (size_t)(4 * d.E + 1 + 2) * sizeof(int);
-  return launch(decode_dispatch_kernel<B, V, false>, dim3((unsigned)d.T * (unsigned)chunks + 1u), dim3(B), lds, s,
-                (const u32x4 *)x, K, window, (float *)nullptr, d, p, chunks);
+  const dim3 grid((unsigned)d.T * (unsigned)(chunks * G) + 1u);
+  if (p.source_count)
+    return launch(decode_dispatch_kernel<B, V, SB, G, false, true>, grid, dim3(B), lds, s, (const u32x4 *)x, K, window,
+                  (float *)nullptr, d, p, chunks, per_group);
+  return launch(decode_dispatch_kernel<B, V, SB, G, false, false>, grid, dim3(B), lds, s, (const u32x4 *)x, K, window,
+                (float *)nullptr, d, p, chunks, per_group);
 }
 
 hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K, const PlanView &p, void *window,
                                   hipStream_t s) {
-  // Every workgroup of a token repeats the token's counting, whose cost grows with the batch: from about
-  // 900 branches on, two vectors per lane (half as many workgroups per token) win; below that, more
-  // workgroups spread the stores over more compute units.  Measured at H = 7168, k = 8 (one / two vectors):
-  // T = 16: 3.8 / 4.1 us, T = 80: 4.8 / 5.1 us, T = 128: 5.7 / 5.5 us, T = 144: 6.4 / 6.0 us.
-  if (d.H16 > MOE_DECODE_BLOCK && d.N >= 896) return launch_decode_dispatch_v<2>(d, x, K, p, window, s);
-  return launch_decode_dispatch_v<MOE_DECODE_VEC>(d, x, K, p, window, s);
+  // With a routing degree of at least 6 the slots of a token are split over 4 workgroups of 8 waves (2 slots
+  // each), or over 2 (4 slots each) once the batch is so large that the counting, which every workgroup of a
+  // token repeats over all ids, outweighs the better spread of the stores.  Measured, k = 8, us per dispatch
+  // (one workgroup per token and chunk / two groups / four groups):
+  //   H = 7168: T = 16: 3.9 / 3.5 / 3.5, T = 64: 4.2 / 4.0 / 4.1, T = 128: 5.4 / 4.9 / 4.8, T = 144: 6.0 / 5.5 / 5.2,
+  //             T = 256: 8.8 / 8.0 / 7.7, T = 512: 16.3 / 14.6 / 14.5;
+  //   H = 4096: T = 128: 4.7 / 4.2 / 4.2, T = 256: 6.3 / 5.7 / 6.2, T = 512: 11.0 / 11.2 / 12.4.
+  if (d.k >= 6) {
+    if (d.N <= 1536) return launch_decode_dispatch_shape<512, 2, 2, 4>(d, x, K, p, window, s);
+    return launch_decode_dispatch_shape<512, 2, 4, 2>(d, x, K, p, window, s);
+  }
+  // Few slots per token: one workgroup per token and chunk.  Every workgroup of a token repeats the
+  // counting, so from about 900 branches on two vectors per lane (half as many chunks) win.
+  if (d.H16 > MOE_DECODE_BLOCK && d.N >= 896)
+    return launch_decode_dispatch_shape<MOE_DECODE_BLOCK, 2, 8, 1>(d, x, K, p, window, s);
+  return launch_decode_dispatch_shape<MOE_DECODE_BLOCK, MOE_DECODE_VEC, 8, 1>(d, x, K, p, window, s);
 }
 
 // Whole-row workgroup shapes for the quantised kernels: (threads, vectors per thread) covering H16 <= 4096.
@@ -403,9 +446,12 @@ hipError_t launch_dispatch_quant(const Dims &d, const void *x, const PlanView &p
 hipError_t launch_decode_dispatch_quant(const Dims &d, const void *x, const int32_t *K, const PlanView &p,
                                         void *window_q, float *window_scale, hipStream_t s) {
   const size_t lds = (size_t)(4 * d.E + 1 + 2) * sizeof(int);
-#define GO(B_, V_)                                                                                                 \
-  return launch(decode_dispatch_kernel<B_, V_, true>, dim3((unsigned)d.T + 1u), dim3(B_), lds, s, (const u32x4 *)x, \
-                K, window_q, window_scale, d, p, 1)
+#define GO(B_, V_)                                                                                               \
+  return p.source_count                                                                                          \
+             ? launch(decode_dispatch_kernel<B_, V_, 8, 1, true, true>, dim3((unsigned)d.T + 1u), dim3(B_), lds, s, \
+                      (const u32x4 *)x, K, window_q, window_scale, d, p, 1, (d.k + 7) / 8 * 8)                      \
+             : launch(decode_dispatch_kernel<B_, V_, 8, 1, true, false>, dim3((unsigned)d.T + 1u), dim3(B_), lds, s, \
+                      (const u32x4 *)x, K, window_q, window_scale, d, p, 1, (d.k + 7) / 8 * 8)
   MOE_QUANT_SHAPES(GO);
 #undef GO
 }
