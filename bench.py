@@ -258,9 +258,9 @@ def mix_ceilings(cfg, iters=30):
     measured with plain kernels that share nothing with the library (ceilings/stream_mix.hip):
     8 reads : 1 write (combine's mix) and 1 read : 8 writes (dispatch's mix) of 16-byte vectors, once with
     purely sequential rows and once with the rows scattered over the expert blocks exactly as this workload's
-    routing scatters them; plus read-only and write-only streams.  Each figure is the better of two launch
-    forms (one workgroup per 2 KB unit / a persistent grid).  GB/s over bytes read + written; loops of
-    identical launches, i.e. the conditions of `kernels` (not of `kernels_in_sequence`)."""
+    routing scatters them; plus read-only and write-only streams.  How workgroups are mapped to the data
+    matters as much as the mix, so each figure is the best of several launch forms (named beside it).
+    GB/s over bytes read + written; loops of identical launches, i.e. the conditions of `kernels`."""
     import numpy as np
     import torch
     import ceilings
@@ -274,30 +274,41 @@ def mix_ceilings(cfg, iters=30):
     order = np.argsort(K, kind="stable")                      # branches in window-row order (expert blocks)
     scattered = np.empty(T * k, np.int32)
     scattered[order] = np.arange(T * k, dtype=np.int32)
-    assert scattered.min() == 0 and scattered.max() == T * k - 1
     tables = {"sequential": torch.arange(T * k, dtype=torch.int32, device="cuda"),
               "scattered": torch.from_numpy(scattered).cuda()}
+    for table in tables.values():
+        ceilings._check_table(table, T * k)
     total = (1 + k) * T * H * cfg.elem_bytes
-    out = {"bytes_per_launch": total, "of": "better of one workgroup per (row, 128-vector chunk) and a "
-           "persistent grid of 2048 workgroups; nontemporal 16-byte accesses"}
-    for name, kind, src, dst in (("read8_write1", ceilings.GATHER, big, small),
-                                 ("read1_write8", ceilings.SCATTER, small, big)):
+    out = {"bytes_per_launch": total,
+           "forms": "gather: (workgroup size, nontemporal loads, mapping); scatter: (table entries per workgroup, "
+                    "nontemporal loads, mapping); mapping 0 = (row, chunk) order, 1 = XCD-affine column slices, "
+                    "2 = each XCD walks a contiguous eighth; stores nontemporal"}
+    for name, fn, forms, src, dst in (("read8_write1", ceilings.gather8, ceilings.GATHER_FORMS, big, small),
+                                      ("read1_write8", ceilings.scatter8, ceilings.SCATTER_FORMS, small, big)):
         for tname, table in tables.items():
-            best = None
-            for grid in (0, 2048):
-                fn = lambda i: ceilings.mix(kind, k, src, table, dst, T, cols, grid=grid)
-                fn(0)
-                ms = event_time_ms(fn, iters)
-                best = ms if best is None else min(best, ms)
+            best, best_form = None, None
+            for form in forms:
+                call = lambda i: fn(form, src, table, dst, T, cols)
+                call(0)
+                ms = event_time_ms(call, iters)
+                if best is None or ms < best:
+                    best, best_form = ms, form
             out[f"{name}_{tname}_us"] = round(best * 1e3, 2)
             out[f"{name}_{tname}_GBps"] = round(total / best / 1e6, 1)
+            out[f"{name}_{tname}_form"] = list(best_form)
     sink = torch.zeros(16, dtype=torch.int32, device="cuda")
-    ceilings.read(big, sink)
-    ms = event_time_ms(lambda i: ceilings.read(big, sink), iters)
-    out["read_only_GBps"] = round(big.numel() * 2 / ms / 1e6, 1)
-    ceilings.write(big)
-    ms = event_time_ms(lambda i: ceilings.write(big), iters)
-    out["write_only_GBps"] = round(big.numel() * 2 / ms / 1e6, 1)
+    for nt in (True, False):
+        ceilings.read(big, sink, nt)
+        ms = event_time_ms(lambda i: ceilings.read(big, sink, nt), iters)
+        out["read_only_GBps"] = max(out.get("read_only_GBps", 0), round(big.numel() * 2 / ms / 1e6, 1))
+        ceilings.write(big, nt)
+        ms = event_time_ms(lambda i: ceilings.write(big, nt), iters)
+        out["write_only_GBps"] = max(out.get("write_only_GBps", 0), round(big.numel() * 2 / ms / 1e6, 1))
+    # the serial model: reads and writes share one bus, so a mix cannot beat bytes_read / read_only + bytes_written / write_only
+    rd, wr = out["read_only_GBps"] * 1e3, out["write_only_GBps"] * 1e3      # bytes per microsecond
+    big_b, small_b = k * T * H * cfg.elem_bytes, T * H * cfg.elem_bytes
+    out["read8_write1_serial_model_us"] = round(big_b / rd + small_b / wr, 2)
+    out["read1_write8_serial_model_us"] = round(small_b / rd + big_b / wr, 2)
     return out
 
 

@@ -35,18 +35,15 @@ def load():
         from paper_2605_06055_amd.binding import _bind_hip_runtime
         _bind_hip_runtime()
         lib = ctypes.CDLL(LIB)
-        vp = ctypes.c_void_p
-        lib.ceil_mix.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, vp, ctypes.c_int, ctypes.c_int,
-                                 ctypes.c_int, vp]
-        lib.ceil_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_int, vp]
-        lib.ceil_write.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, vp]
-        for f in (lib.ceil_mix, lib.ceil_read, lib.ceil_write):
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        lib.ceil_gather8.argtypes = [ci, ci, ci, vp, vp, vp, ci, ci, vp]
+        lib.ceil_scatter8.argtypes = [ci, ci, ci, vp, vp, vp, ci, ci, vp]
+        lib.ceil_write.argtypes = [ci, vp, ctypes.c_size_t, vp]
+        lib.ceil_read.argtypes = [ci, vp, ctypes.c_size_t, vp, vp]
+        for f in (lib.ceil_gather8, lib.ceil_scatter8, lib.ceil_read, lib.ceil_write):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
-
-
-GATHER, SCATTER = 0, 1
 
 
 def _stream():
@@ -54,27 +51,47 @@ def _stream():
     return torch.cuda.current_stream().cuda_stream
 
 
-def mix(kind, n_per_row, src, table, dst, rows, cols, grid=0, plain=False):
-    """One launch of the gather (kind 0) or scatter (kind 1) kernel; the table's entries must lie inside the
-    indexed buffer (checked here, on the host, before anything is launched)."""
-    indexed = src if kind == GATHER else dst
-    other = dst if kind == GATHER else src
-    assert table.numel() == rows * n_per_row and table.dtype.itemsize == 4
-    assert indexed.numel() * indexed.element_size() >= rows * n_per_row * cols * 16
-    assert other.numel() * other.element_size() >= rows * cols * 16
-    rc = load().ceil_mix(kind, n_per_row, int(plain), src.data_ptr(), table.data_ptr(), dst.data_ptr(), rows, cols,
-                         grid, _stream())
+def _check_table(table, n_rows_indexed):
+    """The kernels trust the table: its entries are checked here, once, on the host."""
+    assert table.dtype.itemsize == 4
+    lo, hi = int(table.min().item()), int(table.max().item())
+    assert 0 <= lo and hi < n_rows_indexed, "table entry outside the indexed buffer"
+
+
+# forms tried for each mix: (workgroup size or table entries per workgroup, nontemporal loads, mapping)
+GATHER_FORMS = [(64, True, 0), (128, True, 0), (128, True, 1)]
+SCATTER_FORMS = [(1, False, 1), (1, False, 2), (1, True, 1), (8, False, 0), (8, True, 0)]
+
+
+def gather8(form, src, table, dst, rows, cols):
+    """dst[t] = OR of the 8 rows of src named by table[8t .. 8t+8)."""
+    block, nt, mapping = form
+    assert table.numel() == rows * 8 and src.numel() * src.element_size() >= rows * 8 * cols * 16
+    assert dst.numel() * dst.element_size() >= rows * cols * 16
+    rc = load().ceil_gather8(block, int(nt), mapping, src.data_ptr(), table.data_ptr(), dst.data_ptr(), rows, cols,
+                             _stream())
     if rc:
-        raise RuntimeError(f"ceil_mix launch failed ({rc})")
+        raise RuntimeError(f"ceil_gather8 launch failed ({rc})")
 
 
-def read(src, sink, grid=4096):
-    rc = load().ceil_read(src.data_ptr(), src.numel() * src.element_size() // 16, sink.data_ptr(), grid, _stream())
+def scatter8(form, src, table, dst, rows, cols):
+    """dst[table[8t + j]] = src[t] for j = 0..7."""
+    per_unit, nt, mapping = form
+    assert table.numel() == rows * 8 and dst.numel() * dst.element_size() >= rows * 8 * cols * 16
+    assert src.numel() * src.element_size() >= rows * cols * 16
+    rc = load().ceil_scatter8(per_unit, int(nt), mapping, src.data_ptr(), table.data_ptr(), dst.data_ptr(), rows, cols,
+                              _stream())
+    if rc:
+        raise RuntimeError(f"ceil_scatter8 launch failed ({rc})")
+
+
+def read(src, sink, nt=True):
+    rc = load().ceil_read(int(nt), src.data_ptr(), src.numel() * src.element_size() // 16, sink.data_ptr(), _stream())
     if rc:
         raise RuntimeError(f"ceil_read launch failed ({rc})")
 
 
-def write(dst, grid=4096):
-    rc = load().ceil_write(dst.data_ptr(), dst.numel() * dst.element_size() // 16, grid, _stream())
+def write(dst, nt=False):
+    rc = load().ceil_write(int(nt), dst.data_ptr(), dst.numel() * dst.element_size() // 16, _stream())
     if rc:
         raise RuntimeError(f"ceil_write launch failed ({rc})")
