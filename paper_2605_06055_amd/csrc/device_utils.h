@@ -49,6 +49,16 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
   return v;
 }
 
+// Sum of a 64-bit count (below 2^60) over the 64 lanes of a wave, as three 20-bit limbs through the DPP scan.
+// Every lane of the wave must call; the result is uniform.
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+  const int l0 = (int)(v & 0xFFFFFu), l1 = (int)((v >> 20) & 0xFFFFFu), l2 = (int)(v >> 40);
+  const unsigned s0 = (unsigned)__builtin_amdgcn_readlane(wave_inclusive_scan(l0), kWave - 1);
+  const unsigned s1 = (unsigned)__builtin_amdgcn_readlane(wave_inclusive_scan(l1), kWave - 1);
+  const unsigned s2 = (unsigned)__builtin_amdgcn_readlane(wave_inclusive_scan(l2), kWave - 1);
+  return (unsigned long long)s0 + ((unsigned long long)s1 << 20) + ((unsigned long long)s2 << 40);
+}
+
 // Exclusive prefix sum of total[0..E) into g[0..E], g[E] = grand total; executed by ONE wave
 // (all 64 lanes of it must call).  Each lane owns a run of consecutive experts; E <= 1024.
 // Only the bits of total[] selected by `mask` are counts; `addend` (optional) is added element-wise.

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
   __shared__ int part[(BLOCK / kWave) * SB];            // per-wave packed counts of a slot batch
   __shared__ int part_m[(BLOCK / kWave) * SB];          // per-wave rows of the other source ranks
   __shared__ int part_v[BLOCK / kWave];                         // per-wave number of ids inside [0,E)
-  __shared__ unsigned long long others_rows;                    // rows of the other source ranks, 64-bit
+  __shared__ unsigned long long part_w[BLOCK / kWave];          // per-wave rows of the other source ranks, 64-bit
   constexpr int kWaves = BLOCK / kWave;
   const int per_token = chunks * groups;
   if (blockIdx.x == 0) {                 // the tables workgroup goes first: it is the longest one
@@ -157,9 +157,8 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
   int col_all[kCols], col_pre[kCols], col_id[kCols];
 #pragma unroll
   for (int q2 = 0; q2 < kCols; ++q2) col_all[q2] = col_pre[q2] = 0, col_id[q2] = -1;
+  unsigned long long wave_rows = 0;                  // rows of the other sources counted by this wave's threads
   if (multi) {
-    if (tid == 0) others_rows = 0;
-    __syncthreads();
     unsigned long long wide = 0;
     const int parts = max(1, BLOCK / d.E);          // threads per column when the matrix is narrow
     const int part = parts > 1 ? tid / d.E : 0;
@@ -188,7 +187,7 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
       col_all[q2] = all;
       col_pre[q2] = pre;
     }
-    if (wide) atomicAdd(&others_rows, wide);        // complete once the slot exchange's barrier has passed
+    wave_rows = wave_sum_u64(wide);
   }
   bool overflow = false;                            // rows of all sources together do not fit in int32
 
@@ -258,14 +257,14 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
         part[wave * SB + lane] = mine;
         if (multi) part_m[wave * SB + lane] = mine_m;
       }
-      if (multi && j0 == jg0 && lane == 0) part_v[wave] = n_valid;
+      if (multi && j0 == jg0 && lane == 0) part_v[wave] = n_valid, part_w[wave] = wave_rows;
     }
     __syncthreads();
     if (multi && j0 == jg0) {
-      unsigned own_rows = 0;
+      unsigned long long all_rows = 0;
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) own_rows += (unsigned)part_v[w];
-      overflow = others_rows + own_rows >= (1ull << 31);
+      for (int w = 0; w < kWaves; ++w) all_rows += part_w[w] + (unsigned)part_v[w];
+      overflow = all_rows >= (1ull << 31);
     }
     int packed = 0, ahead_m = 0;
     if (lane < SB) {
@@ -415,8 +414,10 @@ hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K
   //   H = 7168: T = 16: 3.9 / 3.5 / 3.5, T = 64: 4.2 / 4.0 / 4.1, T = 128: 5.4 / 4.9 / 4.8, T = 144: 6.0 / 5.5 / 5.2,
   //             T = 256: 8.8 / 8.0 / 7.7, T = 512: 16.3 / 14.6 / 14.5;
   //   H = 4096: T = 128: 4.7 / 4.2 / 4.2, T = 256: 6.3 / 5.7 / 6.2, T = 512: 11.0 / 11.2 / 12.4.
+  // With several source ranks every workgroup also sums the columns of the count matrix, so two groups are the
+  // better trade there (T = 128, 32 sources: 8.0 / 7.6 / 7.8 us with one / two / four groups).
   if (d.k >= 6) {
-    if (d.N <= 1536) return launch_decode_dispatch_shape<512, 2, 2, 4>(d, x, K, p, window, s);
+    if (d.N <= 1536 && !p.source_count) return launch_decode_dispatch_shape<512, 2, 2, 4>(d, x, K, p, window, s);
     return launch_decode_dispatch_shape<512, 2, 4, 2>(d, x, K, p, window, s);
   }
   // Few slots per token: one workgroup per token and chunk.  Every workgroup of a token repeats the

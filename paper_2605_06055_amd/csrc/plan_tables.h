@@ -46,10 +46,10 @@ __device__ __forceinline__ void sum_columns(const int32_t *__restrict__ src, int
   const int nthreads = blockDim.x;
   const int parts = max(1, nthreads / cols);
   const int tid = threadIdx.x;
-  if (parts > 1 && tid >= parts * cols) return;
+  const bool live = parts == 1 || tid < parts * cols;      // every thread stays for the wave-wide sum below
   const int part = parts == 1 ? 0 : tid / cols;
   unsigned long long wide = 0;
-  for (int col = parts == 1 ? tid : tid - part * cols; col < cols; col += nthreads) {
+  for (int col = parts == 1 ? tid : tid - part * cols; live && col < cols; col += nthreads) {
     int all = 0, bef = 0;
     const int32_t *p = src + col;
     for (int r0 = part; r0 < rows; r0 += parts * 16) {
@@ -69,7 +69,10 @@ __device__ __forceinline__ void sum_columns(const int32_t *__restrict__ src, int
     if (all) atomicAdd(&all_sum[col], all);
     if (before_sum && bef && col < before_cols) atomicAdd(&before_sum[col], bef);
   }
-  if (grand && wide) atomicAdd(grand, wide);
+  if (grand) {                                             // one 64-bit LDS atomic per wave
+    const unsigned long long wave_rows = wave_sum_u64(wide);
+    if (lane_id() == 0 && wave_rows) atomicAdd(grand, wave_rows);
+  }
 }
 
 // Do the rows of all sources together reach 2^31?  others_rows: 64-bit sum of the other sources' counts;
