@@ -119,6 +119,13 @@ typedef struct moe_plan_t {
   int32_t *recv_count;    /* [E]    out, may be NULL: rows of expert e's whole block over all sources (n^exp,
                                     recvTokenNumPerExpert); the rows a rank region receives (n^recv) are its segment sum */
   int32_t *recv_offset;   /* [E+1]  out, may be NULL: first row of expert e's whole block; [E] = one past the last block */
+  int32_t *dispatch_order; /* [2*T*k] optional (NULL: not used): plan state for the PREFILL dispatch.  Where it pays
+                                    (windows of up to 320 MiB with rows of 8 KB or more) the plan also lists the
+                                    placed branches as (token, window row) pairs, sorted by window row inside stretches
+                                    of about 16 MB of X, and moe_dispatch walks that list instead of the tokens: rows
+                                    of one expert are then written together.  Entries of unplaced branches are -1.
+                                    The result of moe_dispatch is the same with or without it.  Content and use are
+                                    decided by the shape alone; a DECODE dispatch leaves a valid list too. */
 } moe_plan_t;
 
 /* Bytes of plan->workspace that moe_plan needs for this shape (multiple of 256, never 0). */

@@ -32,7 +32,8 @@ class _PlanStruct(ctypes.Structure):
                 ("expert_offset", ctypes.c_void_p), ("region_base", ctypes.c_void_p),
                 ("send_idx", ctypes.c_void_p), ("row_map", ctypes.c_void_p), ("status", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-                ("source_count", ctypes.c_void_p), ("recv_count", ctypes.c_void_p), ("recv_offset", ctypes.c_void_p)]
+                ("source_count", ctypes.c_void_p), ("recv_count", ctypes.c_void_p), ("recv_offset", ctypes.c_void_p),
+                ("dispatch_order", ctypes.c_void_p)]
 
 
 def library_path() -> str:
@@ -132,7 +133,8 @@ def moe_resolve_schedule(shape: MoeShape) -> int:
 class MoePlan:
     """Device buffers of ``moe_plan_t`` held as torch tensors (memory plumbing only)."""
 
-    def __init__(self, shape: MoeShape, device="cuda", with_send_idx: bool = True, source_count=None):
+    def __init__(self, shape: MoeShape, device="cuda", with_send_idx: bool = True, source_count=None,
+                 with_order: bool = True):
         import torch
         N = shape.T * shape.k
         i32 = dict(dtype=torch.int32, device=device)
@@ -147,12 +149,13 @@ class MoePlan:
         self.source_count = source_count          # [R,E] int32 counts of the other source ranks, or None
         self.recv_count = torch.empty(shape.E, **i32)
         self.recv_offset = torch.empty(shape.E + 1, **i32)
+        self.dispatch_order = torch.empty(2 * max(N, 1), **i32) if with_order else None
 
     def struct(self) -> _PlanStruct:
         return _PlanStruct(_ptr(self.expert_count), _ptr(self.rank_count), _ptr(self.expert_offset),
                            _ptr(self.region_base), _ptr(self.send_idx), _ptr(self.row_map), _ptr(self.status),
                            _ptr(self.workspace), self.workspace.numel(), _ptr(self.source_count),
-                           _ptr(self.recv_count), _ptr(self.recv_offset))
+                           _ptr(self.recv_count), _ptr(self.recv_offset), _ptr(self.dispatch_order))
 
 
 def _plan_struct(plan) -> _PlanStruct:

@@ -52,6 +52,7 @@ int check_shape(const moe_shape *sh, Dims *d) {
     d->H16 = (int32_t)(row_bytes / 16);
     d->dtype = sh->dtype;
     d->stride = sh->region_stride_rows;
+    d->order_tiles = 0;
   }
   return MOE_OK;
 }
@@ -87,6 +88,8 @@ int check_plan(const moe_plan_t *pl, bool need_tables, PlanView *v) {
   v->source_count = need_tables ? pl->source_count : nullptr;
   v->recv_count = need_tables ? pl->recv_count : nullptr;
   v->recv_offset = need_tables ? pl->recv_offset : nullptr;
+  v->order = pl->dispatch_order;
+  if (!aligned16(pl->dispatch_order)) return MOE_ERR_ALIGN;
   if (need_tables && (!aligned16(pl->source_count) || !aligned16(pl->recv_count) || !aligned16(pl->recv_offset)))
     return MOE_ERR_ALIGN;
   return MOE_OK;
@@ -146,6 +149,7 @@ int plan_call(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan,
   rc = check_plan(plan, true, &v);
   if (rc != MOE_OK) return rc;
   if (!aligned16(topk_idx)) return MOE_ERR_ALIGN;
+  d.order_tiles = v.order ? plan_order_tiles(d) : 0;
   hipStream_t s = (hipStream_t)stream;
   if (d.T == 0) return launch_status(launch_plan_empty(d, v, s));
   int32_t *tile_hist = nullptr;
@@ -215,6 +219,7 @@ int moe_dispatch(const moe_shape *shape, const void *x, const int32_t *topk_idx,
   if (rc != MOE_OK) return rc;
   if (!aligned16(x) || !aligned16(window) || (decode && !aligned16(topk_idx))) return MOE_ERR_ALIGN;
   if (ranges_overlap(x, token_bytes(d), window, window_bytes(d))) return MOE_ERR_OVERLAP;
+  d.order_tiles = v.order ? plan_order_tiles(d) : 0;
   hipStream_t s = (hipStream_t)stream;
   if (d.T == 0) {
     return decode ? launch_status(launch_plan_empty(d, v, s)) : MOE_OK;
@@ -244,6 +249,7 @@ int moe_dispatch_quant(const moe_shape *shape, const void *x, const int32_t *top
         ranges_overlap(window_q, rows * (uint64_t)d.H, window_scale, rows * sizeof(float)))
       return MOE_ERR_OVERLAP;
   }
+  d.order_tiles = v.order ? plan_order_tiles(d) : 0;
   hipStream_t s = (hipStream_t)stream;
   if (d.T == 0) return decode ? launch_status(launch_plan_empty(d, v, s)) : MOE_OK;
   return launch_status(decode ? launch_decode_dispatch_quant(d, x, topk_idx, v, window_q, window_scale, s)

@@ -56,6 +56,31 @@ __global__ __launch_bounds__(BLOCK) void dispatch_slices_kernel(const u32x4 *__r
   }
 }
 
+// Prefill dispatch along the plan's order list: unit p copies column slice c of X[token] to window[row] for
+// the p-th (token, row) pair.  The pairs are sorted by row inside stretches of tokens whose X slices fit the
+// L2 of an XCD, so consecutive workgroups of an XCD write consecutive rows of one expert block and re-read
+// tokens from L2.  U units per workgroup, each with 128 / U lanes, as in dispatch_slices_kernel.
+template <int U>
+__global__ __launch_bounds__(128) void dispatch_list_kernel(const u32x4 *__restrict__ X,
+                                                            const int32_t *__restrict__ order,
+                                                            u32x4 *__restrict__ window, int H16, int slice, int N) {
+  typedef int i32x2 __attribute__((ext_vector_type(2)));
+  constexpr int kLanes = 128 / U;
+  const int unit = U == 1 ? 0 : (int)threadIdx.x / kLanes;
+  const int lane = U == 1 ? (int)threadIdx.x : (int)threadIdx.x % kLanes;
+  const int pidx = (blockIdx.x / kSlices) * U + unit;
+  const int c = blockIdx.x % kSlices;
+  if (pidx >= N) return;
+  i32x2 pair = ((const i32x2 *)order)[pidx];
+  if (kLanes % kWave == 0) pair = i32x2{uniform(pair[0]), uniform(pair[1])};
+  const int t = pair[0], row = pair[1];
+  if (t < 0 || row < 0) return;
+  const int end = min((c + 1) * slice, H16);
+  const u32x4 *src = X + (size_t)t * (size_t)H16;
+  u32x4 *dst = window + (size_t)row * (size_t)H16;
+  for (int col = c * slice + lane; col < end; col += kLanes) store_stream(dst + col, src[col]);
+}
+
 // ---- decode -------------------------------------------------------------------------------------
 //
 // Row of branch (t,j) with expert e:  region/expert base + #{ids i : lo <= K_i < e} + #{i < t*k+j : K_i = e}
@@ -284,6 +309,10 @@ __global__ __launch_bounds__(BLOCK) void decode_dispatch_kernel(const u32x4 *__r
     if (own && c == 0 && wave == 0) {
       if (p.send_idx) p.send_idx[first + j0 + lane] = s;
       p.row_map[first + j0 + lane] = row;
+      if (d.order_tiles > 0) {          // a later prefill-schedule dispatch on this plan walks the order list
+        p.order[2 * (first + j0 + lane)] = t;
+        p.order[2 * (first + j0 + lane) + 1] = row;
+      }
     }
     // fan the chunk out to this batch's destination rows
     const int nb = min(SB, jg1 - j0);
@@ -356,7 +385,19 @@ static hipError_t launch_dispatch_ju(const Dims &d, const void *x, const PlanVie
                 (const int32_t *)p.row_map, (u32x4 *)window, d.k, d.H16, slice, d.N);
 }
 
+static hipError_t launch_dispatch_list(const Dims &d, const void *x, const PlanView &p, void *window, hipStream_t s) {
+  const int slice = (d.H16 + kSlices - 1) / kSlices;
+  const int U = slice > 64 ? 1 : 2;                      // the list is only used with slices of at least 64 vectors
+  const dim3 grid(((unsigned)d.N + U - 1) / U * (unsigned)kSlices);
+  if (U == 1)
+    return launch(dispatch_list_kernel<1>, grid, dim3(128), 0, s, (const u32x4 *)x, (const int32_t *)p.order,
+                  (u32x4 *)window, d.H16, slice, d.N);
+  return launch(dispatch_list_kernel<2>, grid, dim3(128), 0, s, (const u32x4 *)x, (const int32_t *)p.order,
+                (u32x4 *)window, d.H16, slice, d.N);
+}
+
 hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void *window, hipStream_t s) {
+  if (d.order_tiles > 0 && p.order) return launch_dispatch_list(d, x, p, window, s);
   // A workgroup should move a few KB, so that the grid stays within what the dispatcher sustains (about 3000
   // workgroups per microsecond), with its lanes busy.
   //   Normally one unit per workgroup; a unit takes J branches of its token until it moves 4 KB (1.75 KB

@@ -20,6 +20,7 @@ struct PlanView {
   const int32_t *source_count;  // [R*E] or nullptr
   int32_t *recv_count;     // [E] or nullptr
   int32_t *recv_offset;    // [E+1] or nullptr
+  int32_t *order;          // [2*N] (token, row) pairs in dispatch order, or nullptr
 };
 
 struct Dims {
@@ -29,6 +30,7 @@ struct Dims {
   int32_t H16;      // 16-byte vectors per row
   int32_t dtype;
   int64_t stride;   // region_stride_rows (0 = tight)
+  int32_t order_tiles;   // plan tiles per sorted stretch of the dispatch order list (0: the list is not used)
 };
 
 // Branches per plan tile for N routed branches (1024, doubled until at most 512 tiles remain) and the tile count.
@@ -37,6 +39,10 @@ int plan_tile_count(int64_t N);
 // Does launch_plan read and write its tile_hist scratch for N branches?  (Small batches are planned by one
 // launch that counts every id itself and may be given tile_hist == nullptr.)
 bool plan_uses_workspace(int64_t N);
+// Plan tiles per sorted stretch of the dispatch order list for this shape; 0 = dispatch walks the branches in
+// token order and the list is neither written nor read.  Depends on the shape only, so that moe_plan, the
+// decode-schedule dispatch (which leaves a plan) and the prefill-schedule dispatch agree.
+int plan_order_tiles(const Dims &d);
 
 hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s);
 hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, hipStream_t s);

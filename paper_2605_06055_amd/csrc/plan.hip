@@ -85,6 +85,10 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   int *pre = others + E;               // [E]    branches of the source ranks below this one
   int *wcur = pre + E;                 // [waves][E] segment histograms, then running s per wave segment
   int *misc = wcur + kPlanWaves * E;   // [2]    scratch
+  // dispatch order list: counts inside this tile's sorted stretch (a run of d.order_tiles tiles)
+  int *st_total = FUSED ? total : misc + 2;             // [E+1]  branches of expert e in the whole stretch
+  int *st_before = FUSED ? before : st_total + E + 1;   // [E]    ... in the stretch's tiles in front of this one
+  int *st_excl = misc + 2 + (E + 1) + E;                // [E+1]  exclusive scan of st_total over the experts
   __shared__ unsigned long long others_rows;   // rows of the other source ranks, 64-bit
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int me = blockIdx.x;
@@ -109,6 +113,10 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
     return;
   }
 
+  // The sorted stretch this tile belongs to (FUSED: the whole batch is one stretch)
+  const bool ordered = d.order_tiles > 0;
+  const int st0 = ordered ? (me / d.order_tiles) * d.order_tiles : 0;
+  const int st1 = ordered ? min(tiles, st0 + d.order_tiles) : 0;
   const int seg = tile / kPlanWaves;
   const long long seg_start = (long long)me * tile + (long long)wave * seg;
   const int rounds = seg / kWave;
@@ -130,6 +138,8 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   for (int e = tid; e <= E; e += kPlanBlock) total[e] = 0;
   for (int e = tid; e < 3 * E; e += kPlanBlock) before[e] = 0;       // before, others and pre
   for (int x = tid; x < kPlanWaves * E; x += kPlanBlock) wcur[x] = 0;
+  if (!FUSED && ordered)
+    for (int e = tid; e < 2 * E + 1; e += kPlanBlock) st_total[e] = 0;                // st_total and st_before
   __syncthreads();
   if (FUSED) {
     for (int i0 = 0; i0 < d.N; i0 += kBatch * kPlanBlock) {
@@ -148,6 +158,8 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
     }
   } else {
     sum_columns<false>(tile_hist, tiles, E + 1, me, total, before, E);
+    if (ordered)
+      sum_columns<false>(tile_hist + (size_t)st0 * (E + 1), st1 - st0, E + 1, me - st0, st_total, st_before, E);
   }
   if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E, &others_rows);
   // histogram of each wave's segment (counts only: atomics are order-free here)
@@ -158,6 +170,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   }
   __syncthreads();
   if (!FUSED && wave == 0) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
+  if (!FUSED && ordered && wave == 1) wave_exclusive_scan_lds(st_total, st_excl, E);
   // exclusive prefix of the segment counts over the 16 waves, seeded with the count in earlier tiles:
   // element (e, w) sits in lane w of a 16-lane row, so one DPP row scan does it
   for (int x0 = 0; x0 < kPlanWaves * E; x0 += kPlanBlock) {
@@ -173,6 +186,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   __syncthreads();
   if (FUSED) {
     if (wave == 0) wave_exclusive_scan_lds(total, g, E, -1, multi ? others : nullptr);
+    if (ordered && wave == 1) wave_exclusive_scan_lds(st_total, st_excl, E);
     __syncthreads();
   }
 
@@ -200,6 +214,15 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
     if (in) {
       if (p.send_idx) p.send_idx[i] = s;
       p.row_map[i] = row;
+    }
+    if (ordered) {
+      // position of the branch among the counted branches of its stretch, sorted by (expert, flat index), i.e.
+      // by window row; branches that are not counted leave the tail of the stretch's list, which is marked unused
+      typedef int i32x2 __attribute__((ext_vector_type(2)));
+      i32x2 *list = (i32x2 *)p.order;
+      const long long st_base = (long long)st0 * tile;
+      if (valid) list[st_base + st_excl[e] + st_before[e] + (s - before[e])] = i32x2{(int)i / d.k, row};
+      if (in && (int)(i - st_base) >= st_excl[E]) list[i] = i32x2{-1, -1};
     }
     // the next round of this wave must see this round's counter updates
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -247,10 +270,29 @@ hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s) {
 
 bool plan_uses_workspace(int64_t N) { return plan_tile_count(N) > MOE_PLAN_FUSED_MAX_TILES; }
 
+// Measured on the same buffers, k = 8, balanced routing, us per dispatch with the list / in token order (the plan
+// costs 0.6-1 us more when it writes the list): H = 7168: T = 1024 17.8 / 23.0, 2048 36.7 / 41.7, 3072 61.4 / 62.1,
+// 4096 88 / 83.5 (a loss), 5000 96.9 / 101.7; H = 4096: T = 1024 10.8 / 12.9, 2048 20.2 / 25.8, 3072 29.2 / 39.4,
+// 4096 40.8 / 48.8, 5000 51.2 / 62.8.  From windows of about 350 MB on the gain is small or uncertain (it also
+// depends on where the buffers happen to lie), and with very large batches the dependent list lookup only costs:
+// the list is used for windows of up to 320 MiB.  Stretches whose X rows fill about 16 MB (2 MB per XCD, resident
+// in its L2) did best.
+int plan_order_tiles(const Dims &d) {
+  const int64_t row_bytes = (int64_t)d.H16 * 16;
+  if (d.N == 0 || d.H16 < 512) return 0;                            // narrow rows keep the several-branches units
+  if ((int64_t)d.N * row_bytes > ((int64_t)320 << 20)) return 0;    // larger windows gain little or nothing
+  const int tile = plan_tile_size(d.N), tiles = plan_tile_count(d.N);
+  if (!plan_uses_workspace(d.N)) return tiles;                      // single-launch plan: the batch is one stretch
+  int64_t want = ((int64_t)16 << 20) / row_bytes * d.k / tile;      // tiles whose tokens fill 16 MB of X
+  int st = 1;
+  while (st * 2 <= want) st *= 2;
+  return st < tiles ? st : tiles;
+}
+
 template <bool FUSED>
 static hipError_t launch_plan_rank(const Dims &d, const int32_t *K, const PlanView &p, const int32_t *tile_hist,
                                    int tiles, int tile, hipStream_t s) {
-  const size_t lds = (size_t)(5 * d.E + 2 + kPlanWaves * d.E + 2) * sizeof(int);
+  const size_t lds = (size_t)(5 * d.E + 2 + kPlanWaves * d.E + 2 + 3 * d.E + 2) * sizeof(int);
   if (lds > 64 * 1024) {   // beyond the default dynamic LDS limit (E > ~800): raise it once per process
     static const hipError_t raised = hipFuncSetAttribute((const void *)plan_rank_kernel<FUSED>,
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);

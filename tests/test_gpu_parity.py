@@ -465,6 +465,73 @@ def test_seeded_random_shapes(moe):
         _case(moe, K, E, R, sch, H=H, stride=stride, dtype=dtype, seed=case, label=f"fuzz {case}")
 
 
+def check_order_list(order, K, ref, E):
+    """The plan's dispatch order list: every counted branch once as (token, window row), unused entries (-1, -1),
+    rows non-decreasing inside every aligned run of 1024 entries (a piece of one sorted stretch)."""
+    T, k = K.shape
+    N = T * k
+    pairs = order[:2 * N].reshape(N, 2)
+    flat = K.reshape(-1)
+    counted = (flat >= 0) & (flat < E)
+    want = np.stack([np.repeat(np.arange(T), k)[counted], ref.row_map.reshape(-1)[counted]], axis=1)
+    used = pairs[:, 0] >= 0
+    assert used.sum() == counted.sum()
+    assert np.all(pairs[~used] == -1)
+    key = lambda a: a[np.lexsort((a[:, 0], a[:, 1]))]
+    placed_got, placed_want = pairs[used & (pairs[:, 1] >= 0)], want[want[:, 1] >= 0]
+    assert np.array_equal(key(placed_got), key(placed_want))                  # rows are unique: pairs match one to one
+    assert np.array_equal(np.sort(pairs[used & (pairs[:, 1] < 0)][:, 0]), np.sort(want[want[:, 1] < 0][:, 0]))
+    for a in range(0, N, 1024):
+        rows = pairs[a:a + 1024, 1]
+        rows = rows[rows >= 0]
+        assert np.all(np.diff(rows) >= 0), f"list entries {a}.. are not sorted by window row"
+
+
+def test_dispatch_order_list(moe):
+    """Where the shape qualifies (rows of at least 8 KB, window up to 320 MiB) the plan also emits the placed
+    branches sorted by window row inside stretches of tokens, and dispatch walks that list.  The list is checked
+    against the oracle's row map, and dispatch must give the same window with and without it."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    rng = np.random.default_rng(91)
+    cases = [(777, 7168, 8, 256, 32, 0, False),       # one launch plan: the batch is one stretch
+             (3000, 4096, 8, 64, 8, 0, False),        # two launches, two units per workgroup, stretches of 16 tiles
+             (2900, 7168, 8, 256, 32, 0, False),      # just under the window limit: stretches of 8 tiles, ragged last one
+             (2600, 4096, 8, 64, 8, 2000, False),     # fixed stride with dropped branches
+             (2100, 8200, 6, 48, 4, 0, True),         # several source ranks, ragged row tail
+             (1300, 2048, 9, 40, 5, 0, False)]        # fp32 storage below (rows of 8 KB)
+    for (T, H, k, E, R, stride, multi) in cases:
+        fp32 = H == 2048
+        K = wl.random_routing(rng, T, k, E, distinct=k <= E, p_masked=0.03, p_invalid=0.01)
+        Xf = rng.standard_normal((T, H)).astype(np.float32)
+        X = Xf if fp32 else wl.f32_to_bf16_bits(Xf)
+        M = rng.integers(0, 50, size=(R, E)).astype(np.int32) if multi else None
+        me = R // 2
+        ref = oracle.plan_multi(K, M, me, E, R, stride) if multi else oracle.plan(K, E, R, stride)
+        rows = max(1, R * stride if stride else ref.window_rows)
+        windows = []
+        for with_order in (True, False):
+            print(f"[order] T={T} H={H} k={k} E={E} stride={stride} multi={multi} list={with_order}", flush=True)
+            layer = MoeLayer(T, H, k, E, R, dtype=moe.MOE_DTYPE_F32 if fp32 else moe.MOE_DTYPE_BF16,
+                             schedule=moe.MOE_SCHEDULE_PREFILL, region_stride_rows=stride, rank_id=me if multi else 0,
+                             source_count=None if M is None else to_device(M), window_rows=rows)
+            if not with_order:
+                layer.plan.dispatch_order = None
+                layer._plan_struct = layer.plan.struct()
+            else:
+                layer.plan.dispatch_order.fill_(-77)
+            layer.window.view(torch.int16).fill_(0x7B7B)
+            layer.dispatch(to_device(X), to_device(K))
+            torch.cuda.synchronize()
+            assert np.array_equal(to_host(layer.plan.row_map)[:T * k].reshape(T, k), ref.row_map)
+            if with_order:
+                check_order_list(to_host(layer.plan.dispatch_order), K, ref, E)
+            windows.append(to_host(layer.window.view(torch.int16))[:rows])
+        assert windows[0].tobytes() == windows[1].tobytes()
+        fill = np.uint16(0x7B7B) if not fp32 else np.frombuffer(np.array([0x7B7B, 0x7B7B], np.uint16).tobytes(), np.float32)[0]
+        want = oracle.dispatch(X, ref.row_map, rows, fill=fill)
+        assert windows[0].tobytes() == want.tobytes()
+
+
 def test_plan_left_by_decode_dispatch_is_reusable(moe):
     """A later call on identical routing may skip planning: the explicit schedule's dispatch, given the plan
     state a fused decode dispatch left behind, places new payload in the same rows."""
