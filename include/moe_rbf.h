@@ -67,7 +67,7 @@ enum moe_status {
 };
 
 #define MOE_MAX_EXPERTS 1024
-#define MOE_AUTO_DECODE_MAX_BRANCHES 4096
+#define MOE_AUTO_DECODE_MAX_BRANCHES 5120
 #define MOE_DECODE_MAX_BRANCHES 8192
 #define MOE_PLAN_SINGLE_LAUNCH_MAX_BRANCHES 12288 /* up to here moe_plan is one launch and ignores plan->workspace */
 #define MOE_STATIC_SCRATCH_BYTES (1u << 20)       /* device scratch held by the library for moe_plan_static */
@@ -120,9 +120,9 @@ typedef struct moe_plan_t {
                                     recvTokenNumPerExpert); the rows a rank region receives (n^recv) are its segment sum */
   int32_t *recv_offset;   /* [E+1]  out, may be NULL: first row of expert e's whole block; [E] = one past the last block */
   int32_t *dispatch_order; /* [2*T*k] optional (NULL: not used): plan state for the PREFILL dispatch.  Where it pays
-                                    (windows of up to 320 MiB with rows of 8 KB or more) the plan also lists the
+                                    (rows of 12 KB or more with windows of up to 320 MiB, rows of 8 to 12 KB with windows of up to 1100 MiB) the plan also lists the
                                     placed branches as (token, window row) pairs, sorted by window row inside stretches
-                                    of about 16 MB of X, and moe_dispatch walks that list instead of the tokens: rows
+                                    of about 28 MB of X, and moe_dispatch walks that list instead of the tokens: rows
                                     of one expert are then written together.  Entries of unplaced branches are -1.
                                     The result of moe_dispatch is the same with or without it.  Content and use are
                                     decided by the shape alone; a DECODE dispatch leaves a valid list too. */

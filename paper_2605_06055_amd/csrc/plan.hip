@@ -270,23 +270,27 @@ hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s) {
 
 bool plan_uses_workspace(int64_t N) { return plan_tile_count(N) > MOE_PLAN_FUSED_MAX_TILES; }
 
-// Measured on the same buffers, k = 8, balanced routing, us per dispatch with the list / in token order (the plan
-// costs 0.6-1 us more when it writes the list): H = 7168: T = 1024 17.8 / 23.0, 2048 36.7 / 41.7, 3072 61.4 / 62.1,
-// 4096 88 / 83.5 (a loss), 5000 96.9 / 101.7; H = 4096: T = 1024 10.8 / 12.9, 2048 20.2 / 25.8, 3072 29.2 / 39.4,
-// 4096 40.8 / 48.8, 5000 51.2 / 62.8.  From windows of about 350 MB on the gain is small or uncertain (it also
-// depends on where the buffers happen to lie), and with very large batches the dependent list lookup only costs:
-// the list is used for windows of up to 320 MiB.  Stretches whose X rows fill about 16 MB (2 MB per XCD, resident
-// in its L2) did best.
+// Measured on the same buffers, k = 8, us per LAYER (plan + dispatch + combine) with the list / in token order, with
+// stretches of about 28 MB of X (3.5 MB per XCD, most of its L2), which did best:
+//   H = 7168, balanced: T = 1536 69.3 / 75.4, 2048 94.4 / 97.6, 3072 139.0 / 138.5, 4096 182.0 / 182.4,
+//                       6144 262.6 / 265.5, 8192 361.7 / 360.1; Zipf routing: T = 4096 180.1 / 175.4 (a loss)
+//   H = 4096, balanced: T = 2048 59.1 / 61.6, 4096 108.4 / 109.4, 8192 204.4 / 208.5, 16384 390.1 / 418.7;
+//             group-limited, E = 128: T = 8192 202.4 / 205.8, 16384 379.2 / 405.2, 32768 952 / 837 (a loss)
+// A loop of dispatches alone gains far more (T = 4096, H = 7168: 76.8 / 85.2 us), but inside a layer the list and X
+// come in cold and the plan spends 0.6-1 us writing the list, so only these shapes keep a gain:
+// rows of 12 KB or more with windows of up to 320 MiB, narrower rows (at least 8 KB) with windows of up to 1100 MiB.
 int plan_order_tiles(const Dims &d) {
   const int64_t row_bytes = (int64_t)d.H16 * 16;
   if (d.N == 0 || d.H16 < 512) return 0;                            // narrow rows keep the several-branches units
-  if ((int64_t)d.N * row_bytes > ((int64_t)320 << 20)) return 0;    // larger windows gain little or nothing
+  const int64_t limit_mb = row_bytes < 12288 ? 1100 : 320;
+  if ((int64_t)d.N * row_bytes > (limit_mb << 20)) return 0;
   const int tile = plan_tile_size(d.N), tiles = plan_tile_count(d.N);
   if (!plan_uses_workspace(d.N)) return tiles;                      // single-launch plan: the batch is one stretch
-  int64_t want = ((int64_t)16 << 20) / row_bytes * d.k / tile;      // tiles whose tokens fill 16 MB of X
-  int st = 1;
-  while (st * 2 <= want) st *= 2;
-  return st < tiles ? st : tiles;
+  // stretches of about 28 MB of X, all of (nearly) the same length
+  const int64_t most = ((int64_t)28 << 20) / row_bytes * d.k / tile;
+  if (most < 1) return 1;
+  const int64_t n = (tiles + most - 1) / most;
+  return (int)((tiles + n - 1) / n);
 }
 
 template <bool FUSED>

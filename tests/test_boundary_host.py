@@ -46,8 +46,8 @@ def test_sizes_and_schedule():
     assert moe.moe_window_rows(shape(region_stride_rows=100)) == 400
     assert moe.moe_workspace_bytes(s) % 256 == 0 and moe.moe_workspace_bytes(s) >= (16 + 1) * 4
     assert moe.moe_resolve_schedule(s) == moe.MOE_SCHEDULE_DECODE
-    assert moe.moe_resolve_schedule(shape(T=1025)) == moe.MOE_SCHEDULE_PREFILL      # 4100 branches
-    assert moe.moe_resolve_schedule(shape(T=1024)) == moe.MOE_SCHEDULE_DECODE       # 4096 branches
+    assert moe.moe_resolve_schedule(shape(T=1281)) == moe.MOE_SCHEDULE_PREFILL      # 5124 branches
+    assert moe.moe_resolve_schedule(shape(T=1280)) == moe.MOE_SCHEDULE_DECODE       # 5120 branches
     assert moe.moe_resolve_schedule(shape(schedule=moe.MOE_SCHEDULE_PREFILL)) == moe.MOE_SCHEDULE_PREFILL
     big = shape(T=32768, H=4096, k=8, E=128, R=16)
     assert moe.moe_window_rows(big) * 4096 * 2 == 2 ** 31
