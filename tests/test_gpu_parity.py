@@ -507,7 +507,7 @@ def test_dispatch_order_list(moe):
         M = rng.integers(0, 50, size=(R, E)).astype(np.int32) if multi else None
         me = R // 2
         ref = oracle.plan_multi(K, M, me, E, R, stride) if multi else oracle.plan(K, E, R, stride)
-        rows = max(1, R * stride if stride else ref.window_rows)
+        rows = R * stride if stride else max(ref.window_rows, T * k)      # the caller provides moe_window_rows rows
         windows = []
         for with_order in (True, False):
             print(f"[order] T={T} H={H} k={k} E={E} stride={stride} multi={multi} list={with_order}", flush=True)
