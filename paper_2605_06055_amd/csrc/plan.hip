@@ -282,7 +282,10 @@ bool plan_uses_workspace(int64_t N) { return plan_tile_count(N) > MOE_PLAN_FUSED
 int plan_order_tiles(const Dims &d) {
   const int64_t row_bytes = (int64_t)d.H16 * 16;
   if (d.N == 0 || d.H16 < 512) return 0;                            // narrow rows keep the several-branches units
-  const int64_t limit_mb = row_bytes < 12288 ? 1100 : 320;
+#ifndef MOE_ORDER_LIMIT_SCALE
+#define MOE_ORDER_LIMIT_SCALE 1          // tuning knob: scales both window limits
+#endif
+  const int64_t limit_mb = (row_bytes < 12288 ? 1100 : 320) * MOE_ORDER_LIMIT_SCALE;
   if ((int64_t)d.N * row_bytes > (limit_mb << 20)) return 0;
   const int tile = plan_tile_size(d.N), tiles = plan_tile_count(d.N);
   if (!plan_uses_workspace(d.N)) return tiles;                      // single-launch plan: the batch is one stretch
