@@ -223,8 +223,8 @@ def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1, 
     if graph_too and not use_graph:
         # the same layers as one captured graph (kernel nodes only), replayed: what a serving loop that
         # captures its layers would see (no host launch work between the kernels)
-        per_graph = max(n_sets, 10)
-        gms, g = graph_time_ms(s.step, per_graph, max(2, steps // per_graph))
+        per_graph = max(n_sets, 40)          # enough layers per replay that the replay's own launch cost vanishes
+        gms, g = graph_time_ms(s.step, per_graph, max(3, steps // per_graph))
         res["us_per_layer_graph"] = gms * 1e3
         del g
     return res
