@@ -282,12 +282,15 @@ def mix_ceilings(cfg, iters=30):
     out = {"bytes_per_launch": total,
            "forms": "gather: (workgroup size, nontemporal loads, mapping); scatter: (table entries per workgroup, "
                     "nontemporal loads, mapping); mapping 0 = (row, chunk) order, 1 = XCD-affine column slices, "
-                    "2 = each XCD walks a contiguous eighth; stores nontemporal"}
+                    "2 = each XCD walks a contiguous eighth, 3 = one 512-thread workgroup per compute unit that holds "
+                    "the results of 28 units per thread back until their loads are done; stores nontemporal"}
     for name, fn, forms, src, dst in (("read8_write1", ceilings.gather8, ceilings.GATHER_FORMS, big, small),
                                       ("read1_write8", ceilings.scatter8, ceilings.SCATTER_FORMS, small, big)):
         for tname, table in tables.items():
             best, best_form = None, None
             for form in forms:
+                if form[2] == 3 and cols % 64:
+                    continue
                 call = lambda i: fn(form, src, table, dst, T, cols)
                 call(0)
                 ms = event_time_ms(call, iters)

@@ -59,7 +59,7 @@ def _check_table(table, n_rows_indexed):
 
 
 # forms tried for each mix: (workgroup size or table entries per workgroup, nontemporal loads, mapping)
-GATHER_FORMS = [(64, True, 0), (128, True, 0), (128, True, 1)]
+GATHER_FORMS = [(64, True, 0), (128, True, 0), (128, True, 1), (512, True, 3)]      # mapping 3 needs cols % 64 == 0
 SCATTER_FORMS = [(1, False, 1), (1, False, 2), (1, True, 1), (8, False, 0), (8, True, 0)]
 
 

@@ -14,6 +14,9 @@
 //   map 1: workgroup b -> (column slice b % 8, row b / 8): with workgroups handed to the 8 XCDs round-robin,
 //          XCD c only touches slice c of every row
 //   map 2: XCD b % 8 owns a contiguous eighth of the (row, chunk) units and walks it in order
+//   map 3 (gather only): one workgroup of 512 threads per compute unit; a thread works through units
+//          u, u + threads, ... and holds the results of 28 of them in registers before it stores any
+//          (all loads of a round first, then its stores)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -67,6 +70,46 @@ __global__ __launch_bounds__(BLOCK) void gather8_kernel(const u32x4 *__restrict_
   }
 }
 
+// map 3: persistent grid, stores held back.  cols must be a multiple of 64 (a wave stays inside one row).
+// The (row, column) of a thread's next unit is stepped, not divided out, so that nothing slow sits between
+// the loads of one unit and those of the next.
+__global__ __launch_bounds__(512) void gather8_held_kernel(const u32x4 *__restrict__ in, const int32_t *__restrict__ table,
+                                                           u32x4 *__restrict__ out, int rows, int cols) {
+  constexpr int kHeld = 28;
+  const int step = (int)gridDim.x * 512, rows_per_step = step / cols, cols_per_step = step % cols;
+  const long long units = (long long)rows * cols;
+  for (long long first = (long long)blockIdx.x * 512 + threadIdx.x; first < units; first += (long long)step * kHeld) {
+    const int t0 = (int)(first / cols), c0 = (int)(first - (long long)t0 * cols);
+    u32x4 held[kHeld];
+    int t = t0, c = c0;
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i) {
+      if (t < rows) {
+        const int32_t *e = table + (size_t)__builtin_amdgcn_readfirstlane(t) * 8;
+        int r[8];
+        u32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = __builtin_amdgcn_readfirstlane(e[j]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = ld<true>(in + (size_t)r[j] * (size_t)cols + c);
+        u32x4 acc = v[0];
+#pragma unroll
+        for (int j = 1; j < 8; ++j) acc |= v[j];
+        held[i] = acc;
+      }
+      c += cols_per_step, t += rows_per_step;
+      if (c >= cols) c -= cols, ++t;
+    }
+    t = t0, c = c0;
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i) {
+      if (t < rows) st<true>(out + (size_t)t * (size_t)cols + c, held[i]);
+      c += cols_per_step, t += rows_per_step;
+      if (c >= cols) c -= cols, ++t;
+    }
+  }
+}
+
 // J table entries (destination rows) of one input row per workgroup; 8 entries per input row
 template <int BLOCK, int J, bool NT_LOAD>
 __global__ __launch_bounds__(BLOCK) void scatter8_kernel(const u32x4 *__restrict__ in, const int32_t *__restrict__ table,
@@ -108,6 +151,16 @@ extern "C" {
 
 int ceil_gather8(int block, int nt_load, int map, const void *in, const int32_t *table, void *out, int rows, int cols,
                  void *stream) {
+  if (map == 3) {
+    int dev = 0, cus = 0;
+    if (rows < 1 || cols < 64 || cols % 64 != 0 || block != 512) return (int)hipErrorInvalidValue;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+      return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(gather8_held_kernel, dim3(cus), dim3(512), 0, (hipStream_t)stream, (const u32x4 *)in, table,
+                       (u32x4 *)out, rows, cols);
+    return (int)hipGetLastError();
+  }
   const long long per = map == 1 ? 8 : (cols + block - 1) / block;
   long long units = (long long)rows * per;
   if (map == 2) units = (units + 7) / 8 * 8;

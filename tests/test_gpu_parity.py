@@ -225,6 +225,20 @@ def test_special_values_in_combine(moe):
     run_case(moe, X, K, W, np.ones(E, np.float32), E, R, moe.MOE_SCHEDULE_PREFILL, label="special values")
 
 
+@pytest.mark.parametrize("T,H,k,E,R,dtype", [
+    (4000, 4104, 6, 96, 12, np.uint16),      # k = 6; rows of 513 vectors: ragged last wave of every token
+    (3100, 2056, 8, 64, 8, np.float32),      # fp32 storage, rows of 514 vectors
+    (16001, 2048, 8, 32, 4, np.uint16),      # two rounds of the persistent grid with a ragged last round
+])
+def test_combine_streaming_form_with_masked_slots(moe, T, H, k, E, R, dtype):
+    """Launches large enough for combine's deferred-store form (T * H * b / 16 above 1.5 Mi vectors, k of 6 or 8)
+    with masked and out-of-range slots, on row lengths that are not a whole number of waves."""
+    rng = np.random.default_rng(T)
+    K = wl.random_routing(rng, T, k, E, distinct=True, p_masked=0.15, p_invalid=0.02)
+    got = _case(moe, K, E, R, moe.MOE_SCHEDULE_PREFILL, H=H, dtype=dtype, seed=T, label="streaming combine")
+    assert got["status"][0] > 0 and (got["row_map"] == -1).any()
+
+
 def test_run_to_run_determinism(moe):
     cfg = wl.Config("det", T=3000, H=1024, k=8, E=256, R=32, routing="zipf", seed=5)
     a = run_workload(moe, cfg, moe.MOE_SCHEDULE_PREFILL)
