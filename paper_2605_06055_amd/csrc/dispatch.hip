@@ -355,7 +355,9 @@ __global__ __launch_bounds__(BLOCK) void dispatch_quant_rows_kernel(const u32x4 
   for (int x = 0; x < V; ++x) {
     const int col = tid + x * BLOCK;
     has[x] = col < H16;
-    v[x] = has[x] ? load_stream(src + col) : u32x4{0u, 0u, 0u, 0u};
+    // ordinary loads, as in dispatch_slices_kernel: X may stay in the Infinity Cache from one layer to the next
+    // (with streaming loads the headline dispatch takes 61-63 us instead of 47)
+    v[x] = has[x] ? src[col] : u32x4{0u, 0u, 0u, 0u};
   }
   u32x2 q[V];
   const float scale = quantise_row<BLOCK, V>(v, has, q, red);
@@ -468,11 +470,20 @@ hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K
   return launch_decode_dispatch_shape<MOE_DECODE_BLOCK, MOE_DECODE_VEC, 8, 1>(d, x, K, p, window, s);
 }
 
-// Whole-row workgroup shapes for the quantised kernels: (threads, vectors per thread) covering H16 <= 4096.
-#define MOE_QUANT_SHAPES(GO) \
+// Whole-row workgroup shapes (threads, vectors per thread) covering H16 <= 4096, for the quantised kernels.
+// Prefill: one workgroup per token.  (Smaller workgroups with more vectors per thread, and the slots of a token
+// split over 2-4 workgroups as in the decode kernel, change the dispatch by less than 2 % either way.)
+#define MOE_QUANT_ROW_SHAPES(GO) \
   if (d.H16 <= 256) GO(256, 1);  \
   else if (d.H16 <= 512) GO(512, 1);  \
   else if (d.H16 <= 1024) GO(1024, 1); \
+  else if (d.H16 <= 2048) GO(1024, 2); \
+  else GO(1024, 4)
+// Decode: 8 waves where they cover the row, as for the unquantised kernel.
+#define MOE_QUANT_DECODE_SHAPES(GO) \
+  if (d.H16 <= 256) GO(256, 1);  \
+  else if (d.H16 <= 512) GO(512, 1);  \
+  else if (d.H16 <= 1024) GO(512, 2); \
   else if (d.H16 <= 2048) GO(1024, 2); \
   else GO(1024, 4)
 
@@ -481,20 +492,41 @@ hipError_t launch_dispatch_quant(const Dims &d, const void *x, const PlanView &p
 #define GO(B_, V_)                                                                                         \
   return launch(dispatch_quant_rows_kernel<B_, V_>, dim3((unsigned)d.T), dim3(B_), 0, s, (const u32x4 *)x, \
                 (const int32_t *)p.row_map, (u32x2 *)window_q, window_scale, d.k, d.H16)
-  MOE_QUANT_SHAPES(GO);
+  MOE_QUANT_ROW_SHAPES(GO);
 #undef GO
+}
+
+template <int B, int V, int SB, int G>
+static hipError_t launch_decode_quant_shape(const Dims &d, const void *x, const int32_t *K, const PlanView &p,
+                                            void *window_q, float *window_scale, hipStream_t s) {
+  const size_t lds = (size_t)(4 * d.E + 1 + 2) * sizeof(int);
+  const int per_group = ((d.k + G - 1) / G + SB - 1) / SB * SB;
+  const dim3 grid((unsigned)d.T * (unsigned)G + 1u);
+  if (p.source_count)
+    return launch(decode_dispatch_kernel<B, V, SB, G, true, true>, grid, dim3(B), lds, s, (const u32x4 *)x, K, window_q,
+                  window_scale, d, p, 1, per_group);
+  return launch(decode_dispatch_kernel<B, V, SB, G, true, false>, grid, dim3(B), lds, s, (const u32x4 *)x, K, window_q,
+                window_scale, d, p, 1, per_group);
+}
+
+// Slot groups as in launch_decode_dispatch.  Measured, k = 8, us per quantised dispatch, one workgroup of
+// 1024 threads per token / this rule: H = 7168: T = 32: 5.1 / 3.8, T = 128: 6.0 / 5.1, T = 256: 7.4 / 6.9;
+// H = 4096, T = 128: 5.3 / 4.5; H = 2048, T = 128: 5.1 / 4.2.
+template <int B, int V>
+static hipError_t launch_decode_quant_bv(const Dims &d, const void *x, const int32_t *K, const PlanView &p,
+                                         void *window_q, float *window_scale, hipStream_t s) {
+  if (d.k >= 6) {
+    if (d.N <= 1536 && !p.source_count)
+      return launch_decode_quant_shape<B, V, 2, 4>(d, x, K, p, window_q, window_scale, s);
+    return launch_decode_quant_shape<B, V, 4, 2>(d, x, K, p, window_q, window_scale, s);
+  }
+  return launch_decode_quant_shape<B, V, 8, 1>(d, x, K, p, window_q, window_scale, s);
 }
 
 hipError_t launch_decode_dispatch_quant(const Dims &d, const void *x, const int32_t *K, const PlanView &p,
                                         void *window_q, float *window_scale, hipStream_t s) {
-  const size_t lds = (size_t)(4 * d.E + 1 + 2) * sizeof(int);
-#define GO(B_, V_)                                                                                               \
-  return p.source_count                                                                                          \
-             ? launch(decode_dispatch_kernel<B_, V_, 8, 1, true, true>, dim3((unsigned)d.T + 1u), dim3(B_), lds, s, \
-                      (const u32x4 *)x, K, window_q, window_scale, d, p, 1, (d.k + 7) / 8 * 8)                      \
-             : launch(decode_dispatch_kernel<B_, V_, 8, 1, true, false>, dim3((unsigned)d.T + 1u), dim3(B_), lds, s, \
-                      (const u32x4 *)x, K, window_q, window_scale, d, p, 1, (d.k + 7) / 8 * 8)
-  MOE_QUANT_SHAPES(GO);
+#define GO(B_, V_) return launch_decode_quant_bv<B_, V_>(d, x, K, p, window_q, window_scale, s)
+  MOE_QUANT_DECODE_SHAPES(GO);
 #undef GO
 }
 

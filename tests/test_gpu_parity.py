@@ -445,6 +445,37 @@ def test_quantised_dispatch(moe, schedule):
     assert np.isinf(sc).sum() >= 1 and not np.isnan(sc).any()
 
 
+@pytest.mark.parametrize("schedule", ["prefill", "decode"])
+def test_quantised_dispatch_with_several_sources(moe, schedule):
+    """Quantised rows land in the sub-blocks the several-sources plan assigns; the other sources' rows and scales
+    stay untouched."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    sch = moe.MOE_SCHEDULE_PREFILL if schedule == "prefill" else moe.MOE_SCHEDULE_DECODE
+    rng = np.random.default_rng(60)
+    for (T, H, k, E, R) in ((128, 7168, 8, 256, 32), (300, 1024, 8, 64, 8), (50, 520, 3, 12, 4)):
+        cfg = wl.Config("quant-multi", T=T, H=H, k=k, E=E, R=R, seed=T)
+        w = wl.make(cfg)
+        M = rng.integers(0, 30, size=(R, E)).astype(np.int32)
+        me = R // 2
+        ref = oracle.plan_multi(w.K, M, me, E, R)
+        rows = ref.window_rows
+        print(f"[quant multi] T={T} H={H} k={k} E={E} R={R} schedule={schedule} rows={rows}", flush=True)
+        layer = MoeLayer(T, H, k, E, R, schedule=sch, rank_id=me, source_count=to_device(M), window_rows=rows)
+        wq = torch.full((rows, H), 0xAA, dtype=torch.uint8, device="cuda")
+        ws = torch.full((rows,), -1.0, dtype=torch.float32, device="cuda")
+        xd, kd = to_device(w.X), to_device(w.K)
+        if sch == moe.MOE_SCHEDULE_PREFILL:
+            moe.moe_plan(layer.shape, kd, layer.plan)
+        moe.moe_dispatch_quant(layer.shape, xd, kd, layer.plan, wq, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(layer.plan.row_map)[:T * k].reshape(T, k), ref.row_map)
+        assert np.array_equal(to_host(layer.plan.recv_offset), ref.recv_offset)
+        ref_q, ref_s = oracle.dispatch_quant(w.X, ref.row_map, rows, fill=0xAA)
+        assert ws.cpu().numpy().tobytes() == ref_s.tobytes(), "row scales"
+        assert wq.cpu().numpy().tobytes() == ref_q.tobytes(), "fp8 codes"
+        assert (ref_s == -1.0).sum() == rows - T * k          # the other sources' rows were left alone
+
+
 def test_quantised_dispatch_full_prefill(moe):
     run_quant(moe, wl.CONFIGS["prefill"], moe.MOE_SCHEDULE_AUTO)
 
