@@ -302,6 +302,43 @@ def test_hip_graph_replay_matches_eager(moe):
         assert to_host(layer.window).tobytes() == oracle.dispatch(w.X, ref.row_map, ref.window_rows).tobytes(), rep
 
 
+def test_hip_graph_replay_of_a_prefill_layer(moe):
+    """plan -> dispatch -> combine of a streaming-size layer (two-launch plan, sliced dispatch, deferred-store
+    combine) captured once and replayed on changing inputs: every replay equals the eager result and the oracle."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    cfg = wl.CONFIGS["prefill"].with_(T=4096, H=4096, E=64, R=8)
+    layer = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, schedule=moe.MOE_SCHEDULE_PREFILL, separate_expert_out=False)
+    eager = MoeLayer(cfg.T, cfg.H, cfg.k, cfg.E, cfg.R, schedule=moe.MOE_SCHEDULE_PREFILL, separate_expert_out=False)
+    w0 = wl.make(cfg, seed=41)
+    xd, kd, wd = to_device(w0.X), to_device(w0.K), to_device(w0.W)
+
+    def run(l):
+        moe.moe_plan(l.shape, kd, l.plan)
+        l.dispatch(xd, kd)
+        l.combine(wd)
+
+    run(layer)                              # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run(layer)
+    for rep in range(3):
+        w = wl.make(cfg, seed=50 + rep)
+        xd.copy_(to_device(w.X)), kd.copy_(to_device(w.K)), wd.copy_(to_device(w.W))
+        layer.window.zero_(), layer.y.zero_(), layer.plan.row_map.fill_(-3)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        run(eager)
+        torch.cuda.synchronize()
+        ref = oracle.plan(w.K, cfg.E, cfg.R)
+        print(f"[graph prefill] replay {rep}", flush=True)
+        assert np.array_equal(to_host(layer.plan.row_map).reshape(cfg.T, cfg.k), ref.row_map), rep
+        assert to_host(layer.window).tobytes() == oracle.dispatch(w.X, ref.row_map, ref.window_rows).tobytes(), rep
+        assert to_host(layer.y).tobytes() == to_host(eager.y).tobytes(), rep
+        assert max_ulp(to_host(layer.y), w.X) <= 1, rep        # identity expert, weights sum to 1
+
+
 # --------------------------------------------------------------------------- several source ranks (Notify with M)
 
 def run_multi(moe, cfg, M, me, schedule, stride=0, seed=0):
