@@ -133,7 +133,9 @@ __global__ __launch_bounds__(kDeferBlock) void combine_deferred_kernel(const u32
                                                                        const float *__restrict__ W,
                                                                        const int32_t *__restrict__ row_map,
                                                                        u32x4 *__restrict__ Y, int k_arg, int H16,
-                                                                       int cols_pad, int units, int dq, int dr) {
+                                                                       int cols_pad, int units, int dq, int dr,
+                                                                       int first) {
+  // this launch covers units [first, units)
   constexpr int R = kDeferUnits;
   const int k = KFIX > 0 ? KFIX : k_arg;
   constexpr int G = KFIX > 0 ? (KFIX < kGather ? KFIX : kGather) : kGather;
@@ -141,7 +143,7 @@ __global__ __launch_bounds__(kDeferBlock) void combine_deferred_kernel(const u32
   const int g = (int)blockIdx.x * kDeferBlock + (int)threadIdx.x;
   const int32_t *rm = (const int32_t *)__builtin_assume_aligned(row_map, 16);
   const float *wt = (const float *)__builtin_assume_aligned(W, 16);
-  for (long long base = 0; base < units; base += (long long)nthreads * R) {
+  for (long long base = first; base < units; base += (long long)nthreads * R) {
     const long long u0 = base + g;
     const int t0 = (int)(u0 / cols_pad), col0 = (int)(u0 - (long long)t0 * cols_pad);
     u32x4 res[R];
@@ -206,9 +208,21 @@ static hipError_t launch_combine_deferred(const Dims &d, const void *expert_out,
                                           void *y, int cols_pad, int units, hipStream_t s) {
   const int grid = device_cus();
   const int nthreads = grid * kDeferBlock;
+  // Two rounds per launch: the workgroups drift apart over the rounds and reads and writes mix again; a kernel
+  // boundary lines them up.  Measured inside layers, us per combine, one launch / one round per launch / two:
+  // wide (4.6 rounds) 412 / 386 / 391, Zipf T = 16384 (4 rounds) 329 / 325 / 323, balanced T = 16384 332.5 / 331 / 329,
+  // H = 4096: T = 8192 (1.1 rounds) 94.9 / 96.9 / 94.8, T = 16384 (2.3 rounds) 190.0 / 190.6 / 190.4.
+  constexpr int kRoundsPerLaunch = 2;
   auto go = [&](auto kernel) {
-    return launch(kernel, dim3(grid), dim3(kDeferBlock), 0, s, (const u32x4 *)expert_out, W, (const int32_t *)p.row_map,
-                  (u32x4 *)y, d.k, d.H16, cols_pad, units, nthreads / cols_pad, nthreads % cols_pad);
+    const long long per = (long long)nthreads * kDeferUnits * kRoundsPerLaunch;
+    for (long long first = 0; first < units; first += per) {
+      const long long end = first + per < units ? first + per : units;
+      const hipError_t e = launch(kernel, dim3(grid), dim3(kDeferBlock), 0, s, (const u32x4 *)expert_out, W,
+                                  (const int32_t *)p.row_map, (u32x4 *)y, d.k, d.H16, cols_pad, (int)end,
+                                  nthreads / cols_pad, nthreads % cols_pad, (int)first);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
   };
   switch (d.k) {
     case 8: return go(combine_deferred_kernel<DT, 8>);
