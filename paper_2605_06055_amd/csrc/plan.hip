@@ -270,23 +270,30 @@ hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s) {
 
 bool plan_uses_workspace(int64_t N) { return plan_tile_count(N) > MOE_PLAN_FUSED_MAX_TILES; }
 
-// Measured on the same buffers, k = 8, us per LAYER (plan + dispatch + combine) with the list / in token order, with
-// stretches of about 28 MB of X (3.5 MB per XCD, most of its L2), which did best:
-//   H = 7168, balanced: T = 1536 69.3 / 75.4, 2048 94.4 / 97.6, 3072 139.0 / 138.5, 4096 182.0 / 182.4,
-//                       6144 262.6 / 265.5, 8192 361.7 / 360.1; Zipf routing: T = 4096 180.1 / 175.4 (a loss)
+// Measured on the same buffers, k = 8 unless noted, us per LAYER (plan + dispatch + combine) with the list / in token
+// order, with stretches of about 28 MB of X (3.5 MB per XCD, most of its L2), which did best:
+//   H = 7168, balanced: T = 1536 69.3 / 75.4, 2048 94.4 / 97.6, 3072 134.3 / 136.2, 4096 171.3 / 181.1, 5120 221.6 / 220.8,
+//             6144 258.5 / 263.7, 7168 309 / 303.6 (a loss), 8192 352.9 / 347.4 (a loss), 16384 702 / 691.5 (a loss);
+//             Zipf routing: T = 4096 171.1 / 171.0, T = 16384 665 / 660 (a loss); k = 6, T = 4096: 134.6 / 137.2;
+//             k = 4, T = 8192: 194.2 / 190.9 (a loss)
+//   H = 6144: T = 4096 150.5 / 159.7, 6144 227.5 / 242.0, 8192 292.3 / 312.8
+//   H = 8192: T = 4096 192.7 / 201.5, 6144 285.3 / 301.5;  H = 16384: T = 2048 203.7 / 204.6, 3072 289.8 / 303.0
 //   H = 4096, balanced: T = 2048 59.1 / 61.6, 4096 108.4 / 109.4, 8192 204.4 / 208.5, 16384 390.1 / 418.7;
-//             group-limited, E = 128: T = 8192 202.4 / 205.8, 16384 379.2 / 405.2, 32768 952 / 837 (a loss)
-// A loop of dispatches alone gains far more (T = 4096, H = 7168: 76.8 / 85.2 us), but inside a layer the list and X
-// come in cold and the plan spends 0.6-1 us writing the list, so only these shapes keep a gain:
-// rows of 12 KB or more with windows of up to 320 MiB, narrower rows (at least 8 KB) with windows of up to 1100 MiB.
+//             group-limited, E = 128: T = 8192 202.4 / 205.8, 16384 379.2 / 405.2, 32768 940 / 830 (a loss)
+// A loop of dispatches alone gains more (T = 4096, H = 7168: 76.8 / 85.2 us).  Inside a layer the gain depends on
+// X still being in the Infinity Cache when the dispatch starts (the list makes every token row be fetched at
+// k scattered moments of its stretch), so the list is used
+//   for rows of 12 KB or more while X holds at most 96 MiB and the window at most 770 MiB,
+//   for narrower rows (at least 8 KB) with windows of up to 1100 MiB.
 int plan_order_tiles(const Dims &d) {
   const int64_t row_bytes = (int64_t)d.H16 * 16;
   if (d.N == 0 || d.H16 < 512) return 0;                            // narrow rows keep the several-branches units
 #ifndef MOE_ORDER_LIMIT_SCALE
-#define MOE_ORDER_LIMIT_SCALE 1          // tuning knob: scales both window limits
+#define MOE_ORDER_LIMIT_SCALE 1          // tuning knob: scales all limits
 #endif
-  const int64_t limit_mb = (row_bytes < 12288 ? 1100 : 320) * MOE_ORDER_LIMIT_SCALE;
-  if ((int64_t)d.N * row_bytes > (limit_mb << 20)) return 0;
+  const int64_t mib = (int64_t)MOE_ORDER_LIMIT_SCALE << 20;
+  const int64_t window = (int64_t)d.N * row_bytes, x = (int64_t)d.T * row_bytes;
+  if (row_bytes < 12288 ? window > 1100 * mib : (window > 770 * mib || x > 96 * mib)) return 0;
   const int tile = plan_tile_size(d.N), tiles = plan_tile_count(d.N);
   if (!plan_uses_workspace(d.N)) return tiles;                      // single-launch plan: the batch is one stretch
   // stretches of about 28 MB of X, all of (nearly) the same length

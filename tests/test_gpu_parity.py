@@ -570,14 +570,16 @@ def check_order_list(order, K, ref, E):
 
 
 def test_dispatch_order_list(moe):
-    """Where the shape qualifies (rows of at least 8 KB, windows up to 320 MiB or, for rows under 12 KB, 1100 MiB) the plan also emits the placed
+    """Where the shape qualifies (rows of at least 12 KB: X up to 96 MiB and windows up to 770 MiB; rows of 8 to
+    12 KB: windows up to 1100 MiB) the plan also emits the placed
     branches sorted by window row inside stretches of tokens, and dispatch walks that list.  The list is checked
     against the oracle's row map, and dispatch must give the same window with and without it."""
     from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
     rng = np.random.default_rng(91)
     cases = [(777, 7168, 8, 256, 32, 0, False),       # one launch plan: the batch is one stretch
              (6000, 4096, 8, 64, 8, 0, False),        # two launches, two units per workgroup, two stretches of 24 tiles
-             (2900, 7168, 8, 256, 32, 0, False),      # just under the window limit: stretches of 8 tiles, ragged last one
+             (2900, 7168, 8, 256, 32, 0, False),      # two stretches of 12 tiles, ragged last one
+             (7000, 7168, 8, 256, 32, 0, False),      # just under the limit on X (96 MiB): four stretches of 14 tiles
              (2600, 4096, 8, 64, 8, 2000, False),     # fixed stride with dropped branches
              (2100, 8200, 6, 48, 4, 0, True),         # several source ranks, ragged row tail
              (1300, 2048, 9, 40, 5, 0, False)]        # fp32 storage below (rows of 8 KB)
