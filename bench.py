@@ -227,6 +227,20 @@ def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1, 
         gms, g = graph_time_ms(s.step, per_graph, max(3, steps // per_graph))
         res["us_per_layer_graph"] = gms * 1e3
         del g
+        if s.schedule == moe.MOE_SCHEDULE_PREFILL and n_sets == 1 and not quant:
+            # The steps above all read the same X, which the Infinity Cache then still holds from the layer before
+            # (as it would hold a tensor that the preceding operator has just written).  The same layers with X
+            # rotating through 8 copies (more than the cache holds): every dispatch fetches its rows from HBM.
+            xs = [s.x[0]] + [s.x[0].clone() for _ in range(7)]
+            L = s.layers[0]
+
+            def step_x_cold(i):
+                moe.moe_plan(L.shape, s.k[0], L._plan_struct)
+                moe.moe_dispatch(L.shape, xs[i % 8], s.k[0], L._plan_struct, L.window)
+                L.combine(s.w[0])
+            step_x_cold(0)
+            res["us_per_layer_x_cold"] = event_time_ms(step_x_cold, max(16, steps // 16 * 16)) * 1e3
+            del xs
     return res
 
 
@@ -450,6 +464,11 @@ def main():
         "frac_of_hbm_peak_p50": head["frac_of_hbm_peak_p50"],
         "us_per_layer_graph": head.get("us_per_layer_graph"),
         "frac_of_hbm_peak_graph": head.get("frac_of_hbm_peak_graph"),
+        "x_cold": None if "us_per_layer_x_cold" not in main_res else {
+            "us_per_layer": round(main_res["us_per_layer_x_cold"], 2),
+            "frac_of_hbm_peak": round(cfg.payload_bytes / main_res["us_per_layer_x_cold"] / 1e3 / HBM_PEAK_GBS, 4),
+            "what": "the same layers with X rotating through 8 copies, so that no dispatch finds its token rows in "
+                    "the Infinity Cache (the headline steps re-read one X, as after an operator that has just written it)"},
         "kernels": rounded(kern),
         "kernels_in_sequence": main_res.get("kernels_in_sequence"),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
