@@ -157,9 +157,10 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
       }
     }
   } else {
-    sum_columns<false>(tile_hist, tiles, E + 1, me, total, before, E);
     if (ordered)
-      sum_columns<false>(tile_hist + (size_t)st0 * (E + 1), st1 - st0, E + 1, me - st0, st_total, st_before, E);
+      sum_columns_stretch(tile_hist, tiles, E + 1, me, st0, st1, total, before, st_total, st_before, E);
+    else
+      sum_columns<false>(tile_hist, tiles, E + 1, me, total, before, E);
   }
   if (multi) sum_columns<true>(p.source_count, d.R, E, d.me, others, pre, E, &others_rows);
   // histogram of each wave's segment (counts only: atomics are order-free here)

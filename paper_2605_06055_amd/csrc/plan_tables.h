@@ -75,6 +75,46 @@ __device__ __forceinline__ void sum_columns(const int32_t *__restrict__ src, int
   }
 }
 
+// The tile histograms summed once for a workgroup that also emits the dispatch order list: besides the sums
+// over all rows (all_sum) and over the rows in front of `me` (before_sum, columns < before_cols) it needs the
+// same two sums restricted to the rows [st0, st1) of its stretch (st_all, st_before).  Same row split as
+// sum_columns; one pass over the source instead of two.
+__device__ __forceinline__ void sum_columns_stretch(const int32_t *__restrict__ src, int rows, int cols, int me,
+                                                    int st0, int st1, int *all_sum, int *before_sum, int *st_all,
+                                                    int *st_before, int before_cols) {
+  const int nthreads = blockDim.x;
+  const int parts = max(1, nthreads / cols);
+  const int tid = threadIdx.x;
+  if (parts > 1 && tid >= parts * cols) return;
+  const int part = parts == 1 ? 0 : tid / cols;
+  for (int col = parts == 1 ? tid : tid - part * cols; col < cols; col += nthreads) {
+    int all = 0, bef = 0, s_all = 0, s_bef = 0;
+    const int32_t *p = src + col;
+    for (int r0 = part; r0 < rows; r0 += parts * 16) {
+      int v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int r = r0 + u * parts;
+        v[u] = r < rows ? p[(size_t)r * cols] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int r = r0 + u * parts;
+        const int in_stretch = (r >= st0 && r < st1) ? v[u] : 0;
+        all += v[u];
+        s_all += in_stretch;
+        if (r < me) bef += v[u], s_bef += in_stretch;
+      }
+    }
+    if (all) atomicAdd(&all_sum[col], all);
+    if (s_all) atomicAdd(&st_all[col], s_all);
+    if (col < before_cols) {
+      if (bef) atomicAdd(&before_sum[col], bef);
+      if (s_bef) atomicAdd(&st_before[col], s_bef);
+    }
+  }
+}
+
 // Do the rows of all sources together reach 2^31?  others_rows: 64-bit sum of the other sources' counts;
 // all_rows_low: the int32 sum (possibly wrapped) of own + others; this rank's own count is below 2^31, so
 // it is the difference of the two low words.
