@@ -418,6 +418,15 @@ hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void
   int want = slice <= 64 ? 4096 : 1792;
   int U = 1, J = 1;
   while (J < 8 && J * slice_bytes < want && d.k % (2 * J) == 0) J *= 2;
+  // An X larger than the Infinity Cache (256 MiB) comes from HBM whatever ran before.  Reads that miss it are
+  // slow while the chip is saturated with writes, and the units of a (token, slice) all wait on the same lines,
+  // so fewer, larger units do better there: 2 branches per unit, 8 where a slice is a single wave.
+  // Measured, k = 8, us per dispatch with this rule / without: H = 7168: T = 20480 501 / 752, 24576 632 / 915,
+  // 32768 943 / 1292; H = 8192, T = 16384: 400 / 409; H = 4096, T = 65536: 957 / 1064 (J = 4) / 1961 (J = 1).
+  if ((int64_t)d.T * d.H16 * 16 > ((int64_t)256 << 20)) {
+    const int most = slice <= 64 ? 8 : 2;
+    while (J < most && d.k % (2 * J) == 0) J *= 2;
+  }
   if (slice <= 16 || (slice <= 32 && J * slice_bytes < want)) {     // narrow, or the routing degree allows too few branches
     U = 128 / lanes;
     want = 8192;

@@ -138,6 +138,13 @@ def test_full_size_prefill_configs(moe, name):
         assert got["c_exp"].max() > 10 * cfg.N / cfg.E          # the hot experts really are hot
 
 
+@pytest.mark.parametrize("T,H,k,E,R", [(19000, 7168, 2, 64, 8),      # X = 272 MB: two branches per dispatch unit
+                                       (33000, 4096, 8, 128, 16)])   # X = 270 MB, one-wave slices: eight per unit
+def test_batches_larger_than_the_infinity_cache(moe, T, H, k, E, R):
+    """Token rows of more than 256 MiB: the prefill dispatch switches to larger units (it cannot find X cached)."""
+    run_workload(moe, wl.Config("big-x", T=T, H=H, k=k, E=E, R=R, seed=T), moe.MOE_SCHEDULE_PREFILL)
+
+
 # --------------------------------------------------------------------------- several tiles, ragged tails
 
 @pytest.mark.parametrize("T,H,k,E,R", [
