@@ -150,7 +150,7 @@ int moe_plan(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan, 
  * histograms) lives in a device array of MOE_STATIC_SCRATCH_BYTES that is part of the library image, one copy
  * per device, held until the process ends.  The call allocates and frees nothing.
  *   Limit: MOE_ERR_WORKSPACE if moe_workspace_bytes(shape) > MOE_STATIC_SCRATCH_BYTES (with E <= 510 every
- *   shape fits; E = 1024 fits up to 261120 branches); decided on the host before anything is enqueued.
+ *   shape fits; E = 1024 fits up to 522240 branches); decided on the host before anything is enqueued.
  *   The first call on a device looks the array's device address up (hipGetSymbolAddress, no allocation);
  *   make that first call outside stream capture.  A failed lookup returns MOE_ERR_LAUNCH.
  *   Every call on a device shares that device's array.  Nothing in it has to start at zero (each call writes

@@ -28,8 +28,11 @@ constexpr int kPlanWaves = kPlanBlock / kWave;
 constexpr int kPlanMinTile = kPlanBlock;          // one branch per thread
 constexpr int kPlanMaxTiles = 512;
 
+// Every pass-2 workgroup sums the histograms of all tiles, so many tiles cost more than long ones from about
+// 200 000 branches on.  Measured, us per plan with tiles of 1024 / 2048 / 4096 branches: 32 768 branches
+// 9.5 / 10.7 / 13.3, 131 072: 11.9 / 12.1 / 13.6, 262 144: 15.1 / 11.0 / 12.5.
 int plan_tile_size(int64_t N) {
-  int64_t tile = kPlanMinTile;
+  int64_t tile = N >= 196608 ? 2 * kPlanMinTile : kPlanMinTile;
   while ((N + tile - 1) / tile > kPlanMaxTiles) tile *= 2;
   return (int)tile;
 }
@@ -269,7 +272,7 @@ hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s) {
 #define MOE_PLAN_FUSED_MAX_TILES 12
 #endif
 
-bool plan_uses_workspace(int64_t N) { return plan_tile_count(N) > MOE_PLAN_FUSED_MAX_TILES; }
+bool plan_uses_workspace(int64_t N) { return N > (int64_t)MOE_PLAN_FUSED_MAX_TILES * kPlanMinTile; }
 
 // Measured on the same buffers, k = 8 unless noted, us per LAYER (plan + dispatch + combine) with the list / in token
 // order, with stretches of about 28 MB of X (3.5 MB per XCD, most of its L2), which did best:

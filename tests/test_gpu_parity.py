@@ -153,7 +153,8 @@ def test_batches_larger_than_the_infinity_cache(moe, T, H, k, E, R):
     (333, 1032, 3, 1024, 64),    # E at the limit, rows of 129 vectors (ragged chunk)
     (2049, 512, 1, 4, 1),        # k = 1, one region
     (129, 8, 16, 16, 16),        # 16-byte rows, E = R
-    (70001, 8, 8, 64, 8),        # 560008 branches: more than 512 minimum-size plan tiles, so tiles grow
+    (70001, 8, 8, 64, 8),        # 560008 branches: plan tiles of 2048 branches
+    (140001, 8, 8, 64, 8),       # 1120008 branches: more than 512 tiles of 2048, so the tiles grow to 4096
 ])
 @pytest.mark.parametrize("dtype", [wl.DTYPE_BF16, wl.DTYPE_F32])
 def test_ragged_shapes(moe, T, H, k, E, R, dtype):
