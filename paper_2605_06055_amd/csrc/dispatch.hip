@@ -422,7 +422,7 @@ hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void
   // slow while the chip is saturated with writes, and the units of a (token, slice) all wait on the same lines,
   // so fewer, larger units do better there: 2 branches per unit, 8 where a slice is a single wave.
   // Measured, k = 8, us per dispatch with this rule / without: H = 7168: T = 20480 501 / 752, 24576 632 / 915,
-  // 32768 943 / 1292; H = 8192, T = 16384: 400 / 409; H = 4096, T = 65536: 957 / 1064 (J = 4) / 1961 (J = 1).
+  // 32768 943 / 1292; H = 4096, T = 65536: 957 / 1064 (J = 4) / 1961 (J = 1).
   if ((int64_t)d.T * d.H16 * 16 > ((int64_t)256 << 20)) {
     const int most = slice <= 64 ? 8 : 2;
     while (J < most && d.k % (2 * J) == 0) J *= 2;
