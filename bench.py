@@ -234,12 +234,21 @@ def measure(cfg, steps, warmup, n_sets, use_graph=False, schedule=0, sources=1, 
             xs = [s.x[0]] + [s.x[0].clone() for _ in range(7)]
             L = s.layers[0]
 
-            def step_x_cold(i):
+            nbytes = xs[0].numel() * xs[0].element_size()
+
+            def step_x_cold(i, hint=False):
+                if hint:        # moe_plan_t.prefetch: the plan pulls this X into the caches while it runs
+                    L._plan_struct.prefetch, L._plan_struct.prefetch_bytes = xs[i % 8].data_ptr(), nbytes
                 moe.moe_plan(L.shape, s.k[0], L._plan_struct)
                 moe.moe_dispatch(L.shape, xs[i % 8], s.k[0], L._plan_struct, L.window)
                 L.combine(s.w[0])
             step_x_cold(0)
-            res["us_per_layer_x_cold"] = event_time_ms(step_x_cold, max(16, steps // 16 * 16)) * 1e3
+            n_cold = max(16, steps // 16 * 16)
+            res["us_per_layer_x_cold"] = event_time_ms(step_x_cold, n_cold) * 1e3
+            res["us_per_layer_x_cold_prefetch"] = event_time_ms(lambda i: step_x_cold(i, True), n_cold) * 1e3
+            L._plan_struct.prefetch, L._plan_struct.prefetch_bytes = xs[0].data_ptr(), nbytes
+            res["us_per_layer_prefetch_x_warm"] = event_time_ms(s.step, n_cold) * 1e3
+            L._plan_struct.prefetch, L._plan_struct.prefetch_bytes = None, 0
             del xs
     return res
 
@@ -468,7 +477,13 @@ def main():
             "us_per_layer": round(main_res["us_per_layer_x_cold"], 2),
             "frac_of_hbm_peak": round(cfg.payload_bytes / main_res["us_per_layer_x_cold"] / 1e3 / HBM_PEAK_GBS, 4),
             "what": "the same layers with X rotating through 8 copies, so that no dispatch finds its token rows in "
-                    "the Infinity Cache (the headline steps re-read one X, as after an operator that has just written it)"},
+                    "the Infinity Cache (the headline steps re-read one X, as after an operator that has just written it)",
+            "us_per_layer_with_plan_prefetch": round(main_res["us_per_layer_x_cold_prefetch"], 2),
+            "frac_of_hbm_peak_with_plan_prefetch": round(cfg.payload_bytes / main_res["us_per_layer_x_cold_prefetch"]
+                                                         / 1e3 / HBM_PEAK_GBS, 4),
+            "plan_prefetch": "moe_plan_t.prefetch = X: spare workgroups of the plan read X while the plan runs; the "
+                             "headline does not use it, and with X warm it costs: us_per_layer_warm_with_plan_prefetch",
+            "us_per_layer_warm_with_plan_prefetch": round(main_res["us_per_layer_prefetch_x_warm"], 2)},
         "kernels": rounded(kern),
         "kernels_in_sequence": main_res.get("kernels_in_sequence"),
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,

@@ -70,6 +70,7 @@ enum moe_status {
 #define MOE_AUTO_DECODE_MAX_BRANCHES 5120
 #define MOE_DECODE_MAX_BRANCHES 8192
 #define MOE_PLAN_SINGLE_LAUNCH_MAX_BRANCHES 12288 /* up to here moe_plan is one launch and ignores plan->workspace */
+#define MOE_PREFETCH_MAX_BYTES (160u << 20)       /* what moe_plan reads of plan->prefetch at most (well inside the 256 MB Infinity Cache) */
 #define MOE_STATIC_SCRATCH_BYTES (1u << 20)       /* device scratch held by the library for moe_plan_static */
 
 typedef struct moe_shape {
@@ -126,6 +127,16 @@ typedef struct moe_plan_t {
                                     of one expert are then written together.  Entries of unplaced branches are -1.
                                     The result of moe_dispatch is the same with or without it.  Content and use are
                                     decided by the shape alone; a DECODE dispatch leaves a valid list too. */
+  const void *prefetch;    /* optional (NULL: none), read by moe_plan / moe_plan_static only: device memory that the
+                                    call should pull into the cache hierarchy while it plans, normally the x of the
+                                    moe_dispatch that follows.  The plan kernels are latency-bound and leave the
+                                    memory system idle; spare workgroups of the second plan launch read this range
+                                    (nothing is written, no result depends on it).  A dispatch whose token rows are
+                                    not cached runs 15-35 % slower (they are fetched in small pieces while the chip
+                                    is saturated with writes), so a caller that cannot tell whether x is still
+                                    cached from the operator that produced it passes it here.  16-byte aligned. */
+  size_t prefetch_bytes;   /* bytes of `prefetch` that may be read (all of it readable device memory); a multiple
+                                    of 16.  At most MOE_PREFETCH_MAX_BYTES of it are read. */
 } moe_plan_t;
 
 /* Bytes of plan->workspace that moe_plan needs for this shape (multiple of 256, never 0). */

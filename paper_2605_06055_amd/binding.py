@@ -33,7 +33,8 @@ class _PlanStruct(ctypes.Structure):
                 ("send_idx", ctypes.c_void_p), ("row_map", ctypes.c_void_p), ("status", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("source_count", ctypes.c_void_p), ("recv_count", ctypes.c_void_p), ("recv_offset", ctypes.c_void_p),
-                ("dispatch_order", ctypes.c_void_p)]
+                ("dispatch_order", ctypes.c_void_p), ("prefetch", ctypes.c_void_p),
+                ("prefetch_bytes", ctypes.c_size_t)]
 
 
 def library_path() -> str:
@@ -150,12 +151,15 @@ class MoePlan:
         self.recv_count = torch.empty(shape.E, **i32)
         self.recv_offset = torch.empty(shape.E + 1, **i32)
         self.dispatch_order = torch.empty(2 * max(N, 1), **i32) if with_order else None
+        self.prefetch = None                      # tensor that moe_plan should pull into the caches (normally x), or None
 
     def struct(self) -> _PlanStruct:
         return _PlanStruct(_ptr(self.expert_count), _ptr(self.rank_count), _ptr(self.expert_offset),
                            _ptr(self.region_base), _ptr(self.send_idx), _ptr(self.row_map), _ptr(self.status),
                            _ptr(self.workspace), self.workspace.numel(), _ptr(self.source_count),
-                           _ptr(self.recv_count), _ptr(self.recv_offset), _ptr(self.dispatch_order))
+                           _ptr(self.recv_count), _ptr(self.recv_offset), _ptr(self.dispatch_order),
+                           _ptr(self.prefetch),
+                           0 if self.prefetch is None else self.prefetch.numel() * self.prefetch.element_size())
 
 
 def _plan_struct(plan) -> _PlanStruct:

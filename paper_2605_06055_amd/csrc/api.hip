@@ -90,6 +90,7 @@ int check_plan(const moe_plan_t *pl, bool need_tables, PlanView *v) {
   v->recv_offset = need_tables ? pl->recv_offset : nullptr;
   v->order = pl->dispatch_order;
   if (!aligned16(pl->dispatch_order)) return MOE_ERR_ALIGN;
+
   if (need_tables && (!aligned16(pl->source_count) || !aligned16(pl->recv_count) || !aligned16(pl->recv_offset)))
     return MOE_ERR_ALIGN;
   return MOE_OK;
@@ -149,6 +150,14 @@ int plan_call(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan,
   rc = check_plan(plan, true, &v);
   if (rc != MOE_OK) return rc;
   if (!aligned16(topk_idx)) return MOE_ERR_ALIGN;
+  WarmRange warm;
+  if (plan->prefetch && plan->prefetch_bytes > 0) {
+    if (!aligned16(plan->prefetch) || plan->prefetch_bytes % 16 != 0) return MOE_ERR_ALIGN;
+    const size_t bytes = plan->prefetch_bytes < (size_t)MOE_PREFETCH_MAX_BYTES ? plan->prefetch_bytes
+                                                                                : (size_t)MOE_PREFETCH_MAX_BYTES;
+    warm.ptr = plan->prefetch;
+    warm.vecs = (long long)(bytes / 16);
+  }
   d.order_tiles = v.order ? plan_order_tiles(d) : 0;
   hipStream_t s = (hipStream_t)stream;
   if (d.T == 0) return launch_status(launch_plan_empty(d, v, s));
@@ -166,7 +175,7 @@ int plan_call(const moe_shape *shape, const int32_t *topk_idx, moe_plan_t *plan,
       tile_hist = (int32_t *)plan->workspace;
     }
   }
-  return launch_status(launch_plan(d, topk_idx, v, tile_hist, s));
+  return launch_status(launch_plan(d, topk_idx, v, tile_hist, warm, s));
 }
 
 }  // namespace

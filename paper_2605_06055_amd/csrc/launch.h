@@ -23,6 +23,13 @@ struct PlanView {
   int32_t *order;          // [2*N] (token, row) pairs in dispatch order, or nullptr
 };
 
+// Memory that the plan's spare workgroups read while it runs (moe_plan_t.prefetch), kept out of PlanView so
+// that the latency-bound kernels that take a PlanView do not carry it in their arguments.
+struct WarmRange {
+  const void *ptr = nullptr;
+  long long vecs = 0;      // 16-byte vectors
+};
+
 struct Dims {
   int32_t T, H, k, E, R, Er;
   int32_t me;       // this device's source rank
@@ -45,7 +52,8 @@ bool plan_uses_workspace(int64_t N);
 int plan_order_tiles(const Dims &d);
 
 hipError_t launch_plan_empty(const Dims &d, const PlanView &p, hipStream_t s);
-hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, hipStream_t s);
+hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, const WarmRange &warm,
+                       hipStream_t s);
 hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void *window, hipStream_t s);
 hipError_t launch_decode_dispatch(const Dims &d, const void *x, const int32_t *K, const PlanView &p, void *window,
                                   hipStream_t s);

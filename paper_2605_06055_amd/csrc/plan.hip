@@ -78,7 +78,7 @@ __device__ __forceinline__ int row16_inclusive_scan(int v) {
 template <bool FUSED>
 __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__restrict__ K,
                                                                 const int32_t *__restrict__ tile_hist, int tiles,
-                                                                int tile, Dims d, PlanView p) {
+                                                                int tile, Dims d, PlanView p, WarmRange warm) {
   extern __shared__ int lds[];
   const int E = d.E;
   int *total = lds;                    // [E+1]  c^exp, then the number of invalid ids
@@ -98,6 +98,24 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   const bool multi = p.source_count != nullptr;
   if (tid == 0) others_rows = 0;
 
+  if (me > tiles) {                    // spare workgroups: pull the caller's memory (normally X) into the caches
+    constexpr int kPer = 8;            // vectors per thread and trip
+    const u32x4 *src = (const u32x4 *)warm.ptr;
+    const long long wgs = (long long)gridDim.x - tiles - 1, w = me - tiles - 1;
+    const long long chunk = (warm.vecs + wgs - 1) / wgs;
+    const long long lo = w * chunk, hi = min(lo + chunk, warm.vecs);
+    unsigned acc = 0;
+    for (long long i = lo + tid; i < hi; i += (long long)kPlanBlock * kPer) {
+      u32x4 v[kPer];
+#pragma unroll
+      for (int u = 0; u < kPer; ++u)
+        v[u] = i + (long long)u * kPlanBlock < hi ? src[i + (long long)u * kPlanBlock] : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int u = 0; u < kPer; ++u) acc |= v[u][0];
+    }
+    asm volatile("" ::"v"(acc));       // the loads are kept although nothing uses their values
+    return;
+  }
   if (me == tiles) {                   // tables workgroup
     if (FUSED) {
       tables_from_ids_block(K, d, p, lds);
@@ -309,24 +327,28 @@ int plan_order_tiles(const Dims &d) {
 
 template <bool FUSED>
 static hipError_t launch_plan_rank(const Dims &d, const int32_t *K, const PlanView &p, const int32_t *tile_hist,
-                                   int tiles, int tile, hipStream_t s) {
+                                   int tiles, int tile, const WarmRange &warm, hipStream_t s) {
   const size_t lds = (size_t)(5 * d.E + 2 + kPlanWaves * d.E + 2 + 3 * d.E + 2) * sizeof(int);
   if (lds > 64 * 1024) {   // beyond the default dynamic LDS limit (E > ~800): raise it once per process
     static const hipError_t raised = hipFuncSetAttribute((const void *)plan_rank_kernel<FUSED>,
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
     if (raised != hipSuccess) return raised;
   }
-  return launch(plan_rank_kernel<FUSED>, dim3(tiles + 1), dim3(kPlanBlock), lds, s, K, tile_hist, tiles, tile, d, p);
+  // spare workgroups for plan->prefetch: 8192 vectors (128 KB) each
+  const unsigned spare = warm.ptr ? (unsigned)((warm.vecs + 8191) / 8192) : 0u;
+  return launch(plan_rank_kernel<FUSED>, dim3(tiles + 1 + spare), dim3(kPlanBlock), lds, s, K, tile_hist, tiles, tile,
+                d, p, warm);
 }
 
-hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, hipStream_t s) {
+hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, const WarmRange &warm,
+                       hipStream_t s) {
   const int tile = plan_tile_size(d.N);
   const int tiles = plan_tile_count(d.N);
-  if (!plan_uses_workspace(d.N)) return launch_plan_rank<true>(d, K, p, nullptr, tiles, tile, s);
+  if (!plan_uses_workspace(d.N)) return launch_plan_rank<true>(d, K, p, nullptr, tiles, tile, warm, s);
   const size_t lds1 = (size_t)(d.E + 1) * sizeof(int);
   hipError_t err = launch(plan_tile_hist_kernel, dim3(tiles), dim3(kPlanBlock), lds1, s, K, d.N, d.E, tile, tile_hist);
   if (err != hipSuccess) return err;
-  return launch_plan_rank<false>(d, K, p, tile_hist, tiles, tile, s);
+  return launch_plan_rank<false>(d, K, p, tile_hist, tiles, tile, warm, s);
 }
 
 }  // namespace moe_rbf

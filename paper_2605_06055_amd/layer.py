@@ -40,13 +40,18 @@ class MoeLayer:
         self.schedule = B.moe_resolve_schedule(self.shape)
         self.plan = B.MoePlan(self.shape, device=device, source_count=source_count)
         self._plan_struct = self.plan.struct()
+        self.prefetch_x = False
         self.window = torch.empty((max(self.rows, 1), H), dtype=self.torch_dtype, device=device)
         self.expert_out = (torch.empty_like(self.window) if separate_expert_out else self.window)
         self.y = torch.empty((max(T, 1), H), dtype=self.torch_dtype, device=device)
 
     def dispatch(self, x, topk_idx, stream=None):
-        """Plan (prefill schedule only) + dispatch."""
+        """Plan (prefill schedule only) + dispatch.  With ``prefetch_x`` set the plan is told to pull x into the
+        caches while it runs (moe_plan_t.prefetch)."""
         if self.schedule == B.MOE_SCHEDULE_PREFILL:
+            if self.prefetch_x:
+                self._plan_struct.prefetch = B._ptr(x)
+                self._plan_struct.prefetch_bytes = x.numel() * x.element_size()
             B.moe_plan(self.shape, topk_idx, self._plan_struct, stream)
         B.moe_dispatch(self.shape, x, topk_idx, self._plan_struct, self.window, stream)
 

@@ -120,6 +120,9 @@ def test_pointer_alignment():
     assert code(moe.moe_plan, shape(T=4000, **PRE), 0x100, fake_plan(workspace=0x8001), 0) == -3
     assert code(moe.moe_plan, s, 0x100, fake_plan(source_count=0x9004), 0) == -3
     assert code(moe.moe_plan, s, 0x100, fake_plan(recv_offset=0x9008), 0) == -3
+    assert code(moe.moe_plan, s, 0x100, fake_plan(prefetch=0x9008, prefetch_bytes=64), 0) == -3
+    assert code(moe.moe_plan, s, 0x100, fake_plan(prefetch=0x9000, prefetch_bytes=40), 0) == -3
+    assert code(moe.moe_plan_static, s, 0x100, fake_plan(prefetch=0x9004, prefetch_bytes=64), 0) == -3
     assert code(moe.moe_dispatch, s, 0x108, None, fake_plan(), 0x200, 0) == -3
     assert code(moe.moe_dispatch, s, 0x100, None, fake_plan(), 0x202, 0) == -3
     assert code(moe.moe_combine, s, 0x100, 0x204, fake_plan(), 0x300, 0) == -3

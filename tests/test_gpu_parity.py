@@ -624,6 +624,38 @@ def test_dispatch_order_list(moe):
         assert windows[0].tobytes() == want.tobytes()
 
 
+def test_plan_prefetch_changes_nothing(moe):
+    """moe_plan_t.prefetch only makes spare workgroups of the plan read a range of memory: every plan output is
+    what it is without it, for the one-launch and the two-launch plan, for moe_plan_static, for ranges that are
+    not a whole number of workgroup chunks and for ranges beyond what the plan reads at most."""
+    from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
+    for (T, H, k, E, R) in ((1000, 1032, 8, 64, 8), (4096, 2048, 8, 256, 32), (3000, 7168, 8, 256, 32)):
+        cfg = wl.Config("prefetch", T=T, H=H, k=k, E=E, R=R, seed=T)
+        w = wl.make(cfg)
+        ref = oracle.plan(w.K, E, R)
+        xd, kd = to_device(w.X), to_device(w.K)
+        big = torch.zeros((161 << 20) // 4 + 4, dtype=torch.int32, device="cuda")       # more than the plan reads
+        for call in (moe.moe_plan, moe.moe_plan_static):
+            for what in (xd, xd.view(-1)[:T * H - 8 * 37], big):
+                layer = MoeLayer(T, H, k, E, R, schedule=moe.MOE_SCHEDULE_PREFILL)
+                layer.plan.prefetch = what
+                for t in (layer.plan.row_map, layer.plan.send_idx, layer.plan.expert_offset):
+                    t.fill_(-9)
+                print(f"[prefetch] T={T} H={H} {call.__name__} bytes={what.numel() * what.element_size()}", flush=True)
+                call(layer.shape, kd, layer.plan)
+                torch.cuda.synchronize()
+                assert np.array_equal(to_host(layer.plan.row_map)[:T * k].reshape(T, k), ref.row_map)
+                assert np.array_equal(to_host(layer.plan.send_idx)[:T * k].reshape(T, k), ref.s)
+                assert np.array_equal(to_host(layer.plan.expert_offset), ref.expert_offset)
+                assert np.array_equal(to_host(layer.plan.status)[:3], ref.status)
+        # a whole layer through MoeLayer with the hint switched on
+        layer = MoeLayer(T, H, k, E, R, schedule=moe.MOE_SCHEDULE_PREFILL)
+        layer.prefetch_x = True
+        layer.dispatch(xd, kd)
+        torch.cuda.synchronize()
+        assert to_host(layer.window).tobytes() == oracle.dispatch(w.X, ref.row_map, ref.window_rows).tobytes()
+
+
 def test_plan_left_by_decode_dispatch_is_reusable(moe):
     """A later call on identical routing may skip planning: the explicit schedule's dispatch, given the plan
     state a fused decode dispatch left behind, places new payload in the same rows."""
