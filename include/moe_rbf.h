@@ -70,7 +70,9 @@ enum moe_status {
 #define MOE_AUTO_DECODE_MAX_BRANCHES 5120
 #define MOE_DECODE_MAX_BRANCHES 8192
 #define MOE_PLAN_SINGLE_LAUNCH_MAX_BRANCHES 12288 /* up to here moe_plan is one launch and ignores plan->workspace */
-#define MOE_PREFETCH_MAX_BYTES (160u << 20)       /* what moe_plan reads of plan->prefetch at most (well inside the 256 MB Infinity Cache) */
+#ifndef MOE_PREFETCH_MAX_BYTES
+#define MOE_PREFETCH_MAX_BYTES (224u << 20)       /* what moe_plan reads of plan->prefetch at most (the Infinity Cache holds 256 MB) */
+#endif
 #define MOE_STATIC_SCRATCH_BYTES (1u << 20)       /* device scratch held by the library for moe_plan_static */
 
 typedef struct moe_shape {

@@ -634,7 +634,7 @@ def test_plan_prefetch_changes_nothing(moe):
         w = wl.make(cfg)
         ref = oracle.plan(w.K, E, R)
         xd, kd = to_device(w.X), to_device(w.K)
-        big = torch.zeros((161 << 20) // 4 + 4, dtype=torch.int32, device="cuda")       # more than the plan reads
+        big = torch.zeros((225 << 20) // 4 + 4, dtype=torch.int32, device="cuda")       # more than the plan reads
         for call in (moe.moe_plan, moe.moe_plan_static):
             for what in (xd, xd.view(-1)[:T * H - 8 * 37], big):
                 layer = MoeLayer(T, H, k, E, R, schedule=moe.MOE_SCHEDULE_PREFILL)
