@@ -16,7 +16,7 @@
 //                            are used for COUNTS only, which do not depend on order.  One extra workgroup
 //                            writes the count/offset tables.
 // Both kernels are latency-bound (a few microseconds): loads are requested before LDS is cleared and
-// the serial chain is kept to three barriers.  Small batches skip pass 1 (see plan_rank_kernel<true>).
+// the serial chain is kept to three barriers.  Small batches skip pass 1 (see plan_rank_kernel with FUSED).
 #include "device_utils.h"
 #include "launch.h"
 #include "plan_tables.h"
@@ -75,7 +75,9 @@ __device__ __forceinline__ int row16_inclusive_scan(int v) {
 // FUSED: there was no pass 1.  Every workgroup counts the ids outside its own tile itself (in front of the
 // tile -> `before`, behind it -> `total`), which costs N LDS atomics per workgroup instead of a launch:
 // worth it for batches of up to about twelve thousand branches.
-template <bool FUSED>
+// WARM: the grid carries spare workgroups that read the caller's prefetch range (compiled apart so that the
+// usual plan carries none of it).
+template <bool FUSED, bool WARM>
 __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__restrict__ K,
                                                                 const int32_t *__restrict__ tile_hist, int tiles,
                                                                 int tile, Dims d, PlanView p, WarmRange warm) {
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_rank_kernel(const int32_t *__
   const bool multi = p.source_count != nullptr;
   if (tid == 0) others_rows = 0;
 
-  if (me > tiles) {                    // spare workgroups: pull the caller's memory (normally X) into the caches
+  if (WARM && me > tiles) {            // spare workgroups: pull the caller's memory (normally X) into the caches
     constexpr int kPer = 8;            // vectors per thread and trip
     const u32x4 *src = (const u32x4 *)warm.ptr;
     const long long wgs = (long long)gridDim.x - tiles - 1, w = me - tiles - 1;
@@ -330,14 +332,22 @@ static hipError_t launch_plan_rank(const Dims &d, const int32_t *K, const PlanVi
                                    int tiles, int tile, const WarmRange &warm, hipStream_t s) {
   const size_t lds = (size_t)(5 * d.E + 2 + kPlanWaves * d.E + 2 + 3 * d.E + 2) * sizeof(int);
   if (lds > 64 * 1024) {   // beyond the default dynamic LDS limit (E > ~800): raise it once per process
-    static const hipError_t raised = hipFuncSetAttribute((const void *)plan_rank_kernel<FUSED>,
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    static const hipError_t raised = [] {
+      hipError_t e = hipFuncSetAttribute((const void *)plan_rank_kernel<FUSED, false>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+      return e != hipSuccess ? e
+                             : hipFuncSetAttribute((const void *)plan_rank_kernel<FUSED, true>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    }();
     if (raised != hipSuccess) return raised;
   }
+  if (!warm.ptr)
+    return launch(plan_rank_kernel<FUSED, false>, dim3(tiles + 1), dim3(kPlanBlock), lds, s, K, tile_hist, tiles, tile,
+                  d, p, warm);
   // spare workgroups for plan->prefetch: 8192 vectors (128 KB) each
-  const unsigned spare = warm.ptr ? (unsigned)((warm.vecs + 8191) / 8192) : 0u;
-  return launch(plan_rank_kernel<FUSED>, dim3(tiles + 1 + spare), dim3(kPlanBlock), lds, s, K, tile_hist, tiles, tile,
-                d, p, warm);
+  const unsigned spare = (unsigned)((warm.vecs + 8191) / 8192);
+  return launch(plan_rank_kernel<FUSED, true>, dim3(tiles + 1 + spare), dim3(kPlanBlock), lds, s, K, tile_hist, tiles,
+                tile, d, p, warm);
 }
 
 hipError_t launch_plan(const Dims &d, const int32_t *K, const PlanView &p, int32_t *tile_hist, const WarmRange &warm,
