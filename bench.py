@@ -6,6 +6,9 @@ A step is one pass of the whole hot path over one synthetic batch:
     decode schedule  : moe_dispatch (plan fused) -> moe_combine  (2 calls, 2 kernels)
 with all inputs resident in HBM.  The stand-in expert that fills expert_out runs once, untimed.
 `value` = algorithmic payload bytes of one step, 2*T*H*b*(1+k), divided by the step time.
+Every step of a prefill workload reads the same X, so the Infinity Cache may still hold it from the step
+before (as it holds a tensor that the preceding operator has just written); `x_cold` reports the headline
+layer with X rotating through 8 copies, without and with the plan's prefetch hint.
 
 Prints ONE JSON line on stdout (headline workload); details go to stderr.
 """
