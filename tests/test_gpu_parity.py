@@ -555,6 +555,25 @@ def test_seeded_random_shapes(moe):
         _case(moe, K, E, R, sch, H=H, stride=stride, dtype=dtype, seed=case, label=f"fuzz {case}")
 
 
+def test_seeded_large_shapes(moe):
+    """Seeded shapes of the size where the prefill path changes form: two-launch plan, order list on and off,
+    deferred-store combine, with masked / invalid ids and sometimes a fixed stride.  MOE_FUZZ_LARGE_CASES /
+    MOE_FUZZ_SEED run a longer or a different series."""
+    rng = np.random.default_rng(int(os.environ.get("MOE_FUZZ_SEED", "2025")) + 1)
+    for case in range(int(os.environ.get("MOE_FUZZ_LARGE_CASES", "5"))):
+        H = int(rng.choice([2048, 4096, 5128, 6144, 7168, 8192]))
+        k = int(rng.choice([4, 6, 8]))
+        R = int(rng.choice([4, 8, 32]))
+        E = R * int(rng.choice([2, 8]))
+        T = int(rng.integers(1600, 7000))
+        K = wl.random_routing(rng, T, k, E, distinct=True, p_masked=float(rng.choice([0, 0.05])),
+                              p_invalid=float(rng.choice([0, 0.01])))
+        stride = 0
+        if rng.random() < 0.25:
+            stride = max(1, int(oracle.plan(K, E, R).c_rank.max() * rng.uniform(0.8, 1.2)))
+        _case(moe, K, E, R, moe.MOE_SCHEDULE_PREFILL, H=H, stride=stride, seed=case, label=f"large fuzz {case}")
+
+
 def check_order_list(order, K, ref, E):
     """The plan's dispatch order list: every counted branch once as (token, window row), unused entries (-1, -1),
     rows non-decreasing inside every aligned run of 1024 entries (a piece of one sorted stretch)."""
