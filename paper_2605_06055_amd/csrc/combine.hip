@@ -8,6 +8,8 @@
 // ascending j with one fused multiply-add per branch, rounds once and stores 16 bytes.  Every window
 // row is read exactly once and Y is written exactly once, in token order: no un-permute buffer.
 // Row ids and weights are uniform per workgroup and live in scalar registers.
+#include <atomic>
+
 #include "device_utils.h"
 #include "launch.h"
 #include "moe_rbf.h"
@@ -190,17 +192,18 @@ __global__ __launch_bounds__(kDeferBlock) void combine_deferred_kernel(const u32
   }
 }
 
-// Compute units of the current device (asked once per device; no allocation).
+// Compute units of the current device (asked once per device; no allocation).  Calls may come from several host
+// threads: the cache holds the same value whoever fills it.
 static int device_cus() {
-  static int cus[64] = {0};
+  static std::atomic<int> cus[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cus[dev] == 0) {
-    int n = 0;
+  int n = cus[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
-    cus[dev] = n;
+    cus[dev].store(n, std::memory_order_relaxed);
   }
-  return cus[dev];
+  return n;
 }
 
 template <int DT>
