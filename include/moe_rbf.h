@@ -123,7 +123,7 @@ typedef struct moe_plan_t {
                                     recvTokenNumPerExpert); the rows a rank region receives (n^recv) are its segment sum */
   int32_t *recv_offset;   /* [E+1]  out, may be NULL: first row of expert e's whole block; [E] = one past the last block */
   int32_t *dispatch_order; /* [2*T*k] optional (NULL: not used): plan state for the PREFILL dispatch.  Where it pays
-                                    (rows of 12 KB or more while x holds at most 96 MiB and the window at most 770 MiB; rows of 8 to 12 KB with windows of up to 1100 MiB) the plan also lists the
+                                    (rows of 12 KB or more while x holds at most 96 MiB and the window at most 770 MiB; rows of 8 to 12 KB and of 2 to 4 KB with windows of up to 1100 MiB) the plan also lists the
                                     placed branches as (token, window row) pairs, sorted by window row inside stretches
                                     of about 28 MB of X, and moe_dispatch walks that list instead of the tokens: rows
                                     of one expert are then written together.  Entries of unplaced branches are -1.

@@ -389,14 +389,21 @@ static hipError_t launch_dispatch_ju(const Dims &d, const void *x, const PlanVie
 }
 
 static hipError_t launch_dispatch_list(const Dims &d, const void *x, const PlanView &p, void *window, hipStream_t s) {
+  // units per workgroup: as many as fit 128 lanes (a unit has as many lanes as its slice has vectors, rounded up
+  // to a power of two, at least 16)
   const int slice = (d.H16 + kSlices - 1) / kSlices;
-  const int U = slice > 64 ? 1 : 2;                      // the list is only used with slices of at least 64 vectors
+  const int U = slice > 64 ? 1 : slice > 32 ? 2 : slice > 16 ? 4 : 8;
   const dim3 grid(((unsigned)d.N + U - 1) / U * (unsigned)kSlices);
-  if (U == 1)
-    return launch(dispatch_list_kernel<1>, grid, dim3(128), 0, s, (const u32x4 *)x, (const int32_t *)p.order,
-                  (u32x4 *)window, d.H16, slice, d.N);
-  return launch(dispatch_list_kernel<2>, grid, dim3(128), 0, s, (const u32x4 *)x, (const int32_t *)p.order,
-                (u32x4 *)window, d.H16, slice, d.N);
+  auto go = [&](auto kernel) {
+    return launch(kernel, grid, dim3(128), 0, s, (const u32x4 *)x, (const int32_t *)p.order, (u32x4 *)window, d.H16,
+                  slice, d.N);
+  };
+  switch (U) {
+    case 1: return go(dispatch_list_kernel<1>);
+    case 2: return go(dispatch_list_kernel<2>);
+    case 4: return go(dispatch_list_kernel<4>);
+    default: return go(dispatch_list_kernel<8>);
+  }
 }
 
 hipError_t launch_dispatch(const Dims &d, const void *x, const PlanView &p, void *window, hipStream_t s) {

@@ -308,10 +308,15 @@ bool plan_uses_workspace(int64_t N) { return N > (int64_t)MOE_PLAN_FUSED_MAX_TIL
 // X still being in the Infinity Cache when the dispatch starts (the list makes every token row be fetched at
 // k scattered moments of its stretch), so the list is used
 //   for rows of 12 KB or more while X holds at most 96 MiB and the window at most 770 MiB,
-//   for narrower rows (at least 8 KB) with windows of up to 1100 MiB.
+//   for narrower rows (8 to 12 KB, and 2 to 4 KB) with windows of up to 1100 MiB.
+// Rows of 2 to 4 KB, us per layer with the list / in token order: H = 2048: T = 8192 105.4 / 108.0, 16384 197.0 / 204.3,
+// 32768 388.6 / 407.6; H = 1024: T = 16384 110.0 / 113.4, 65536 405.7 / 426.0.  Rows in between: H = 3072: T = 8192
+// 162.6 / 163.6, 16384 311.4 / 313.0; H = 2560, T = 8192: 145.6 / 138.5 (a loss).
 int plan_order_tiles(const Dims &d) {
   const int64_t row_bytes = (int64_t)d.H16 * 16;
-  if (d.N == 0 || d.H16 < 512) return 0;                            // narrow rows keep the several-branches units
+  // rows of 2 to 4 KB (slices of 16 to 32 vectors) and rows of at least 8 KB; in between (slices of 33 to 63
+  // vectors, which fill neither one nor two units of a workgroup) and below, token order does as well or better
+  if (d.N == 0 || d.H16 < 128 || (d.H16 > 256 && d.H16 < 512)) return 0;
 #ifndef MOE_ORDER_LIMIT_SCALE
 #define MOE_ORDER_LIMIT_SCALE 1          // tuning knob: scales all limits
 #endif

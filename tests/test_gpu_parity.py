@@ -598,7 +598,7 @@ def check_order_list(order, K, ref, E):
 
 def test_dispatch_order_list(moe):
     """Where the shape qualifies (rows of at least 12 KB: X up to 96 MiB and windows up to 770 MiB; rows of 8 to
-    12 KB: windows up to 1100 MiB) the plan also emits the placed
+    12 KB and of 2 to 4 KB: windows up to 1100 MiB) the plan also emits the placed
     branches sorted by window row inside stretches of tokens, and dispatch walks that list.  The list is checked
     against the oracle's row map, and dispatch must give the same window with and without it."""
     from paper_2605_06055_amd.layer import MoeLayer, to_device, to_host
@@ -609,7 +609,10 @@ def test_dispatch_order_list(moe):
              (7000, 7168, 8, 256, 32, 0, False),      # just under the limit on X (96 MiB): four stretches of 14 tiles
              (2600, 4096, 8, 64, 8, 2000, False),     # fixed stride with dropped branches
              (2100, 8200, 6, 48, 4, 0, True),         # several source ranks, ragged row tail
-             (1300, 2048, 9, 40, 5, 0, False)]        # fp32 storage below (rows of 8 KB)
+             (1300, 2048, 9, 40, 5, 0, False),        # fp32 storage below (rows of 8 KB)
+             (5000, 2040, 8, 64, 8, 0, False),        # rows of 255 vectors: four units of 32 lanes per workgroup
+             (3000, 1024, 8, 32, 4, 0, False),        # rows of 2 KB: eight units of 16 lanes per workgroup
+             (2000, 1544, 6, 48, 4, 900, True)]       # rows of 193 vectors (ragged slices), fixed stride, several sources
     for (T, H, k, E, R, stride, multi) in cases:
         fp32 = H == 2048
         K = wl.random_routing(rng, T, k, E, distinct=k <= E, p_masked=0.03, p_invalid=0.01)
